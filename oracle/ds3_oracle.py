@@ -1,0 +1,221 @@
+"""Plain, slow, obviously-correct CPU oracle for the fine-grained FP8 linear layer.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only tests, the smoke check and
+the benchmark's ``cpu_baseline`` leg may import it; the GPU library never does,
+and this file imports nothing from the GPU package.  It shares no code, table
+or constant generator with the HIP kernels.
+
+What it follows (DeepSeek-V3 technical report, arXiv 2412.19437):
+
+* Section 3.3.2, "Fine-Grained Quantization": the max-abs of each group of
+  elements is mapped to the largest representable FP8 value; activations are
+  grouped 1x128 (per token, per 128 channels), weights 128x128.
+* Section 3.3.2, "Mantissa over Exponents": every tensor uses E4M3.
+* Section 3.3.2, "Online Quantization": the max-abs is taken from the data at
+  hand, so the quantizers are stateless.
+* Section 3.3.2, "Increasing Accumulation Precision": per-group scaling factors
+  along the GEMM inner dimension are multiplied in as the de-quantisation step
+  at every N_C = 128 interval; accumulation is high precision.
+* Section 3.3.3, "Low-Precision Activation" (1): in the backward pass
+  activations are tiled 128x1, i.e. the group of 128 runs along tokens.
+* Section 3.3.1: GEMM outputs are BF16 or FP32 (the oracle leaves its result
+  unrounded in FP64; the comparison tolerance covers the output rounding).
+
+Readings where the paper is silent (all are repeated in the design notes):
+
+* "maximum representable value of FP8" = 448, the OCP E4M3 maximum.
+* The stored factor is the de-quantisation scale  s = fl32(amax / 448).
+* Elements are scaled by one FP32 multiply with r = fl32(448 / amax), then
+  rounded to nearest-even onto the E4M3 grid; magnitudes that would round
+  above 448 saturate to 448; the sign bit is always copied.
+* An all-zero group stores s = 1 and (signed) zero codes.
+* A ragged trailing group is simply smaller.
+* Inputs must be finite.
+
+Pins (tests marked "not gpu"): closed form over all 256 codes, round trip of
+all finite codes, every midpoint tie, brute-force nearest-neighbour search,
+PyTorch's CPU float8_e4m3fn cast as a third opinion, an independent
+exact-rational implementation of the quantizers and the GEMM on tiny shapes,
+power-of-two exactness, scale-invariance, transposition identities, and the
+"all scales 1 equals the plain product" identity.  No function in this file
+is parity-unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+E4M3_MAX = 448.0        # largest finite OCP E4M3 magnitude (S.1111.110)
+TILE = 128              # N_C of Section 3.3.2
+
+
+# --------------------------------------------------------------------------
+# OCP E4M3 ("FN" flavour: no infinities, 0x7F / 0xFF are NaN)
+# --------------------------------------------------------------------------
+def e4m3_decode(codes) -> np.ndarray:
+    """Exact value of each E4M3 code as float64.
+
+    Format definition: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits;
+    exponent field 0 is subnormal (mantissa * 2^-9); S.1111.111 is NaN.
+    """
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where((c & 0x80) != 0, -1.0, 1.0)
+    efield = (c >> 3) & 0xF
+    mant = (c & 0x7).astype(np.float64)
+    normal = np.ldexp(1.0 + mant / 8.0, (efield - 7).astype(np.int64))
+    subnormal = mant * 2.0 ** -9
+    val = sign * np.where(efield == 0, subnormal, normal)
+    return np.where((c & 0x7F) == 0x7F, np.nan, val)
+
+
+def e4m3_encode_rne_sat(y) -> np.ndarray:
+    """Round finite float values to the nearest E4M3 value, ties to the even
+    code, saturating at +-448; returns the uint8 codes.  The sign bit of the
+    input is always copied (so -0.0 and negative underflow give 0x80)."""
+    y = np.asarray(y)
+    if not np.all(np.isfinite(y)):
+        raise ValueError("oracle precondition: finite inputs")
+    neg = np.signbit(y)
+    a = np.abs(y.astype(np.float64))
+    # binade of a: a = m * 2^ex with m in [0.5, 1)  ->  floor(log2 a) = ex - 1
+    _, ex = np.frexp(a)
+    e = np.maximum(ex.astype(np.int64) - 1, -6)      # below 2^-6 the grid is the subnormal one
+    quantum = np.ldexp(1.0, e - 3)                   # spacing of the grid in that binade
+    n = np.rint(a / quantum)                         # exact division; rint is ties-to-even
+    v = np.minimum(n * quantum, E4M3_MAX)            # a carry to 16*quantum is just the next binade
+    # value -> code
+    _, ex2 = np.frexp(v)
+    e2 = ex2.astype(np.int64) - 1
+    is_sub = v < 2.0 ** -6
+    sub_code = np.rint(v * 2.0 ** 9).astype(np.int64)                 # 0..7
+    mant = np.rint((v / np.ldexp(1.0, e2) - 1.0) * 8.0).astype(np.int64)
+    norm_code = ((e2 + 7) << 3) | mant
+    code = np.where(is_sub, sub_code, norm_code)
+    code = np.where(neg, code | 0x80, code)
+    return code.astype(np.uint8)
+
+
+# --------------------------------------------------------------------------
+# Quantizers (Section 3.3.2, Fine-Grained Quantization / Online Quantization)
+# --------------------------------------------------------------------------
+def _quant_groups(xg: np.ndarray, axes):
+    """Quantize groups.  ``xg`` is float32; the max-abs is taken over ``axes``
+    (kept as size-1 axes for broadcasting).  Returns (codes, scales)."""
+    if xg.dtype != np.float32:
+        raise TypeError("quantizer input must be float32 (BF16 widens exactly)")
+    if not np.all(np.isfinite(xg)):
+        raise ValueError("oracle precondition: finite inputs")
+    amax = np.max(np.abs(xg), axis=axes, keepdims=True).astype(np.float32)
+    zero = amax == np.float32(0)
+    safe = np.where(zero, np.float32(1), amax)
+    s = np.where(zero, np.float32(1), safe / np.float32(E4M3_MAX)).astype(np.float32)
+    r = np.where(zero, np.float32(0), np.float32(E4M3_MAX) / safe).astype(np.float32)
+    y = (xg * r).astype(np.float32)                  # one FP32 multiply per element
+    return e4m3_encode_rne_sat(y), s
+
+
+def _pad_to(x: np.ndarray, rows: int, cols: int) -> np.ndarray:
+    out = np.zeros((rows, cols), dtype=x.dtype)
+    out[: x.shape[0], : x.shape[1]] = x
+    return out
+
+
+def quant_act_1x128(x):
+    """1x128 tiles: per row (token), per 128 contiguous columns (channels).
+    x: float32 [M][K].  Returns codes uint8 [M][K], scales float32 [M][ceil(K/128)].
+    Zero padding of a ragged last tile changes neither its max-abs nor its
+    codes, so padding implements "the group is simply smaller"."""
+    x = np.asarray(x)
+    m, k = x.shape
+    kb = -(-k // TILE)
+    xp = _pad_to(x, m, kb * TILE).reshape(m, kb, TILE)
+    q, s = _quant_groups(xp, axes=(2,))
+    return q.reshape(m, kb * TILE)[:, :k].copy(), s.reshape(m, kb)
+
+
+def quant_act_128x1(x):
+    """128x1 tiles: the group of 128 runs along rows (tokens), one column
+    (channel) wide.  x: float32 [T][C].  Returns the *transposed* results:
+    codes uint8 [C][T] (token-contiguous) and scales float32 [C][ceil(T/128)],
+    the layout the weight-gradient GEMM contracts over."""
+    x = np.asarray(x)
+    t, c = x.shape
+    tb = -(-t // TILE)
+    xp = _pad_to(x, tb * TILE, c).reshape(tb, TILE, c)
+    q, s = _quant_groups(xp, axes=(1,))
+    q = q.reshape(tb * TILE, c)[:t, :]
+    return np.ascontiguousarray(q.T), np.ascontiguousarray(s.reshape(tb, c).T)
+
+
+def quant_w_128x128(w):
+    """128x128 blocks: per 128 output channels (rows) per 128 input channels
+    (columns).  w: float32 [N][K].  Returns codes uint8 [N][K] and scales
+    float32 [ceil(N/128)][ceil(K/128)]."""
+    w = np.asarray(w)
+    n, k = w.shape
+    nb, kb = -(-n // TILE), -(-k // TILE)
+    wp = _pad_to(w, nb * TILE, kb * TILE).reshape(nb, TILE, kb, TILE)
+    q, s = _quant_groups(wp, axes=(1, 3))
+    return q.reshape(nb * TILE, kb * TILE)[:n, :k].copy(), s.reshape(nb, kb)
+
+
+# --------------------------------------------------------------------------
+# Block-scaled GEMM (Section 3.3.2, Increasing Accumulation Precision)
+# --------------------------------------------------------------------------
+def dequant_rows(codes, scales) -> np.ndarray:
+    """decode(codes[i][k]) * scales[i][k // 128] in float64 (per-row, per-K-block scales)."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    k = codes.shape[1]
+    s = np.repeat(np.asarray(scales, dtype=np.float32).astype(np.float64), TILE, axis=1)[:, :k]
+    return e4m3_decode(codes) * s
+
+
+def dequant_blocks(codes, scales) -> np.ndarray:
+    """decode(codes[n][k]) * scales[n // 128][k // 128] in float64 (128x128 block scales)."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    n, k = codes.shape
+    s = np.asarray(scales, dtype=np.float32).astype(np.float64)
+    s = np.repeat(np.repeat(s, TILE, axis=0)[:n, :], TILE, axis=1)[:, :k]
+    return e4m3_decode(codes) * s
+
+
+def gemm_fp8_bs(a, sa, b, sb, sb_per_row: bool = False, c_in=None) -> np.ndarray:
+    """Y[m][n] = sum_k (dec(a[m][k]) sa[m][k/128]) * (dec(b[n][k]) sb[..][k/128]) in float64.
+
+    a: codes [M][K], sa: [M][K/128]; b: codes [N][K];
+    sb: [ceil(N/128)][K/128] (weights, block scales) or, with ``sb_per_row``,
+    [N][K/128] (the weight-gradient GEMM, where both operands carry 128x1
+    tiles along the contracted token axis).  ``c_in`` (float) is added when
+    given: gradients are accumulated in FP32 outside the FP8 domain
+    (Section 3.3.3, optimizer states).  The result is left unrounded."""
+    ad = dequant_rows(a, sa)
+    bd = dequant_rows(b, sb) if sb_per_row else dequant_blocks(b, sb)
+    y = ad @ bd.T
+    if c_in is not None:
+        y = y + np.asarray(c_in).astype(np.float64)
+    return y
+
+
+def grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb) -> np.ndarray:
+    """Per expert g: rows [off[g], off[g+1]) of ``a`` times expert g's weight
+    b[g] ([N][K] codes) with block scales sb[g].  Section 2.1.2: experts see
+    only the tokens routed to them; no token is dropped, so groups are ragged
+    and may be empty."""
+    a = np.asarray(a)
+    off = np.asarray(group_offsets, dtype=np.int64)
+    n = np.asarray(b).shape[1]
+    y = np.zeros((a.shape[0], n), dtype=np.float64)
+    for g in range(len(off) - 1):
+        lo, hi = int(off[g]), int(off[g + 1])
+        if hi > lo:
+            y[lo:hi] = gemm_fp8_bs(a[lo:hi], np.asarray(sa)[lo:hi], b[g], sb[g])
+    return y
+
+
+def swiglu(h) -> np.ndarray:
+    """SwiGLU of the fused gate|up projection output (Section 3.3.3 names the
+    operator; the split is the reading: first half of the columns is the gate,
+    second half is up).  out[r][j] = silu(h[r][j]) * h[r][I + j], float64."""
+    h = np.asarray(h).astype(np.float64)
+    inter = h.shape[1] // 2
+    g, u = h[:, :inter], h[:, inter:]
+    return g / (1.0 + np.exp(-g)) * u
