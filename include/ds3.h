@@ -1,0 +1,200 @@
+/*
+ * ds3.h -- C ABI of the fine-grained FP8 linear layer for AMD MI355X (gfx950).
+ *
+ * The operations are those of Section 3.3 of the DeepSeek-V3 technical report
+ * (arXiv 2412.19437):
+ *   - Section 3.3.2 "Fine-Grained Quantization" / "Online Quantization":
+ *     activations are grouped 1x128 (per token, per 128 channels), weights
+ *     128x128; the max-abs of each group is mapped to the largest E4M3 value.
+ *   - Section 3.3.3 "Low-Precision Activation" (1): in the backward pass the
+ *     group of 128 runs along tokens (128x1 tiles).
+ *   - Section 3.3.2 "Increasing Accumulation Precision": the GEMM multiplies
+ *     the per-group scales in along the inner dimension at every N_C = 128
+ *     interval and accumulates in FP32.
+ *   - Section 3.3.1: Fprop, Dgrad and Wgrad take FP8 inputs and produce BF16
+ *     or FP32 outputs.
+ *
+ * Common rules
+ *   - Every data pointer is DEVICE memory owned by the caller.  The library
+ *     allocates nothing, keeps no state between calls and retains no pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they never synchronise and never read
+ *     device data on the host.
+ *   - Argument errors are found on the host before anything is launched and
+ *     reported as a status code; no kernel runs in that case.  Problems of
+ *     size zero (no rows, no columns, an empty expert) are DS3_OK no-ops.
+ *   - Leading dimensions (ld*) are in ELEMENTS of the array they belong to.
+ *   - FP8 codes are OCP E4M3 bytes (bias 7, max 448, no infinities).
+ *   - Quantisation of one group G (arithmetic in FP32, bit-exact contract):
+ *         amax = max |x_i| over G
+ *         s    = amax / 448          (stored de-quantisation scale; 1 if amax == 0)
+ *         r    = 448 / amax          (0 if amax == 0)
+ *         q_i  = E4M3_round_to_nearest_even(x_i * r)   (sign always copied)
+ *     Both divisions are correctly rounded.  Inputs must be finite and nonzero
+ *     magnitudes must lie in [2^-100, 2^100]; otherwise codes and scales are
+ *     unspecified (but nothing faults).  A ragged trailing group is simply
+ *     smaller.
+ */
+#ifndef DS3_H
+#define DS3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DS3_OK = 0,
+    DS3_ERR_NULL = 1,        /* a required pointer is NULL                       */
+    DS3_ERR_SHAPE = 2,       /* negative size, ld smaller than the row, K % 128  */
+    DS3_ERR_ALIGN = 3,       /* pointer / ld / column count not vector aligned   */
+    DS3_ERR_DTYPE = 4,       /* unknown dtype, or accumulate into a BF16 output  */
+    DS3_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (2^31 bytes per operand row span etc.) */
+    DS3_ERR_LAUNCH = 6       /* the HIP runtime refused the launch               */
+} ds3_status;
+
+typedef enum { DS3_F32 = 0, DS3_BF16 = 1 } ds3_dtype;
+
+/* How the scales of the second GEMM operand are indexed. */
+typedef enum {
+    DS3_BSCALE_128x128 = 0, /* sb[(n / 128) * sb_stride_row + kb * sb_stride_kb]: weight blocks (Fprop, Dgrad) */
+    DS3_BSCALE_PER_ROW = 1  /* sb[ n        * sb_stride_row + kb * sb_stride_kb]: 128x1 tiles (Wgrad)          */
+} ds3_bscale;
+
+/*
+ * 1x128 activation quantizer (Section 3.3.2, Fine-Grained Quantization (1)).
+ *   x  [rows][ldx]  FP32 or BF16 (xt), `cols` valid columns per row.
+ *   q  [rows][ldq]  E4M3 codes, same logical shape as x.
+ *   s  scale of tile (row, kb) is s[row * s_stride_row + kb * s_stride_kb],
+ *      kb = column / 128, kb < ceil(cols / 128).  Any two strides that do not
+ *      make tiles overlap are accepted; (1, rows) gives the K-block-major
+ *      layout the GEMM reads fastest.
+ * Alignment: x, q 16-byte aligned; ldx * sizeof(element), ldq and
+ * cols * sizeof(element) multiples of 16 bytes (cols % 8 == 0 for BF16,
+ * cols % 4 == 0 for FP32).
+ */
+ds3_status ds3_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx,
+                               uint8_t* q, int64_t ldq,
+                               float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+
+/*
+ * 128x1 activation quantizer (Section 3.3.3, Low-Precision Activation (1)):
+ * the group of 128 runs along rows (tokens), one column (channel) wide.  The
+ * results are written TRANSPOSED so that the token axis, which the
+ * weight-gradient GEMM contracts over, is contiguous.
+ *   x    [rows][ldx]  FP32 or BF16, rows = tokens, cols = channels.
+ *   q_t  [cols][ldq]  code of (token t, channel c) at q_t[c * ldq + t].
+ *   s_t  scale of (channel c, token block tb) at s_t[c * s_stride_col + tb * s_stride_tb],
+ *        tb < ceil(rows / 128).
+ * Alignment: x 16-byte aligned, ldx and cols as for the 1x128 call; q_t
+ * 16-byte aligned and ldq % 16 == 0.  `rows` is arbitrary.
+ */
+ds3_status ds3_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx,
+                               uint8_t* q_t, int64_t ldq,
+                               float* s_t, int64_t s_stride_col, int64_t s_stride_tb, void* stream);
+
+/*
+ * 128x128 weight quantizer (Section 3.3.2, Fine-Grained Quantization (2)).
+ *   w  [n][ldw]  FP32 or BF16, `k` valid columns.
+ *   q  [n][ldq]  codes.
+ *   s  [ceil(n/128)][ceil(k/128)] row-major, one scale per block.
+ * Alignment as for the 1x128 call.  n and k may be ragged (partial blocks).
+ */
+ds3_status ds3_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw,
+                               uint8_t* q, int64_t ldq, float* s, void* stream);
+
+/*
+ * Block-scaled FP8 GEMM (Section 3.3.2, Increasing Accumulation Precision;
+ * Section 3.3.1 for the three uses Fprop / Dgrad / Wgrad):
+ *
+ *   C[m][n] (+)= sum over kb of  sa(m,kb) * sb(n,kb) * sum_{k in block kb} dec(a[m][k]) * dec(b[n][k])
+ *
+ * with FP32 accumulation and the scale product applied to each 128-long
+ * partial sum.  Both operands are K-contiguous.
+ *   a  [M][lda] codes, sa(m,kb) = sa[m * sa_stride_row + kb * sa_stride_kb]
+ *   b  [N][ldb] codes, sb(n,kb) per `sb_mode` (see ds3_bscale)
+ *   c  [M][ldc] BF16 (round to nearest even) or FP32 (ct).
+ *   accumulate != 0: C += result; FP32 output only (gradient accumulation,
+ *   Section 3.3.3 keeps gradients in FP32).
+ * Requirements: K % 128 == 0; a, b 16-byte aligned and lda, ldb % 16 == 0;
+ * c 16-byte aligned and ldc % 4 == 0.  M and N are arbitrary.
+ * `workspace` is reserved for split-K variants; pass what
+ * ds3_gemm_workspace_bytes() asks for (currently 0, NULL is accepted).
+ * The order of the FP32 additions is unspecified (results are deterministic
+ * for a given shape, but not bit-comparable across shapes).
+ */
+ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K,
+                           const uint8_t* a, int64_t lda,
+                           const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                           const uint8_t* b, int64_t ldb,
+                           const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode,
+                           void* c, ds3_dtype ct, int64_t ldc, int accumulate,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Grouped block-scaled GEMM over MoE experts (Section 2.1.2: each routed
+ * expert multiplies only the tokens routed to it; no token is dropped, so
+ * groups are ragged and may be empty).  For expert g, rows
+ * [group_offsets[g], group_offsets[g+1]) of `a` are multiplied by that
+ * expert's weight b[g] with its 128x128 block scales:
+ *   a   [total_rows][lda] codes, sa as in ds3_gemm_fp8_bs
+ *   b   [G][N][ldb] codes (expert stride N * ldb)
+ *   sb  [G][ceil(N/128)][K/128] row-major
+ *   c   [total_rows][ldc] BF16 or FP32
+ *   group_offsets  DEVICE array of G+1 int32, nondecreasing, [0] == 0 and
+ *                  [G] <= total_rows; it is read on the device only.
+ * Rows at or beyond group_offsets[G] are left untouched.
+ */
+ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                   int64_t N, int64_t K,
+                                   const uint8_t* a, int64_t lda,
+                                   const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                   const uint8_t* b, int64_t ldb, const float* sb,
+                                   void* c, ds3_dtype ct, int64_t ldc,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Tuning hooks: the same two operations with the tile configuration chosen by
+ * the caller instead of by shape.  `variant` in [0, ds3_gemm_num_variants());
+ * -1 selects by shape exactly as the plain calls do.  Results of different
+ * variants agree to FP32 summation-order differences only.
+ */
+int ds3_gemm_num_variants(void);
+ds3_status ds3_gemm_fp8_bs_v(int variant, int64_t M, int64_t N, int64_t K,
+                             const uint8_t* a, int64_t lda,
+                             const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                             const uint8_t* b, int64_t ldb,
+                             const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode,
+                             void* c, ds3_dtype ct, int64_t ldc, int accumulate,
+                             void* workspace, size_t workspace_bytes, void* stream);
+ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                     int64_t N, int64_t K,
+                                     const uint8_t* a, int64_t lda,
+                                     const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                     const uint8_t* b, int64_t ldb, const float* sb,
+                                     void* c, ds3_dtype ct, int64_t ldc,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device workspace the GEMM calls need for this shape (0 today). */
+size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * SwiGLU between the two expert GEMMs (Section 3.3.3, Low-Precision
+ * Activation (2) names the operator): h is the BF16 output of the fused
+ * gate|up projection, [rows][ldh] with 2*inter valid columns, gate in
+ * columns [0, inter), up in [inter, 2*inter);
+ *   out[r][j] = bf16( silu(h[r][j]) * h[r][inter + j] ),  silu(g) = g / (1 + exp(-g)),
+ * computed in FP32.  inter % 8 == 0, pointers 16-byte aligned, ldh, ldo % 8 == 0.
+ */
+ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
+                      void* out, int64_t ldo, void* stream);
+
+/* Static, never NULL. */
+const char* ds3_status_string(ds3_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DS3_H */

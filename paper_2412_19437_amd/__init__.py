@@ -1,0 +1,198 @@
+"""Python binding of libds3: the fine-grained FP8 linear layer of DeepSeek-V3
+(Section 3.3) as hand-written HIP kernels for MI355X (gfx950).
+
+The functions here have the names of the C entry points declared in
+include/ds3.h and only marshal arguments: torch tensors supply device memory
+and the current stream, every step of the path runs in the library's kernels.
+There is no CPU fallback: importing this package without a built libds3.so
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libds3.so")
+
+DS3_OK = 0
+DS3_F32, DS3_BF16 = 0, 1
+DS3_BSCALE_128x128, DS3_BSCALE_PER_ROW = 0, 1
+
+SYMBOLS = [
+    "ds3_quant_act_1x128", "ds3_quant_act_128x1", "ds3_quant_w_128x128",
+    "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_gemm_fp8_bs_v", "ds3_grouped_gemm_fp8_bs_v",
+    "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_swiglu", "ds3_status_string",
+]
+
+
+class Ds3Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2412_19437_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    lib.ds3_quant_act_1x128.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_quant_act_128x1.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_quant_w_128x128.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
+    gemm = [i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, i64, i64, i32, vp, i32, i64, i32, vp, sz, vp]
+    lib.ds3_gemm_fp8_bs.argtypes = gemm
+    lib.ds3_gemm_fp8_bs_v.argtypes = [i32] + gemm
+    grouped = [i32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i32, i64, vp, sz, vp]
+    lib.ds3_grouped_gemm_fp8_bs.argtypes = grouped
+    lib.ds3_grouped_gemm_fp8_bs_v.argtypes = [i32] + grouped
+    lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
+    lib.ds3_gemm_num_variants.argtypes = []
+    lib.ds3_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.ds3_gemm_workspace_bytes.restype = sz
+    lib.ds3_status_string.argtypes = [i32]
+    lib.ds3_status_string.restype = ctypes.c_char_p
+    for name in SYMBOLS:
+        getattr(lib, name)
+    return lib
+
+
+_lib = None
+
+
+def _L() -> ctypes.CDLL:
+    """The loaded library (loaded on first use, so that the build module can be
+    imported before the library exists); raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        _lib = _load()
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _L().ds3_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != DS3_OK:
+        raise Ds3Error(status, where)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DS3_F32
+    if t.dtype == torch.bfloat16:
+        return DS3_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _rows2d(t: torch.Tensor, name: str):
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+
+
+def _scales(rows: int, blocks: int, device, k_major: bool) -> torch.Tensor:
+    """Logical [rows][blocks] FP32 tensor; k_major stores it as [blocks][rows]."""
+    if k_major:
+        return torch.empty((blocks, rows), dtype=torch.float32, device=device).t()
+    return torch.empty((rows, blocks), dtype=torch.float32, device=device)
+
+
+def ds3_quant_act_1x128(x: torch.Tensor, k_major_scales: bool = True):
+    """x [M][K] FP32/BF16 -> (codes uint8 [M][K], scales FP32 logical [M][ceil(K/128)])."""
+    m, k, ldx = _rows2d(x, "x")
+    q = torch.empty((m, k), dtype=torch.uint8, device=x.device)
+    s = _scales(m, (k + 127) // 128, x.device, k_major_scales)
+    st = _L().ds3_quant_act_1x128(x.data_ptr(), _dt(x), m, k, ldx, q.data_ptr(), k,
+                                 s.data_ptr(), s.stride(0), s.stride(1), _stream())
+    _check(st, "ds3_quant_act_1x128")
+    return q, s
+
+
+def ds3_quant_act_128x1(x: torch.Tensor, k_major_scales: bool = True):
+    """x [T][C] -> (codes uint8 [C][T] token-contiguous, scales logical [C][ceil(T/128)])."""
+    t, c, ldx = _rows2d(x, "x")
+    ldq = (t + 15) // 16 * 16
+    q_t = torch.empty((c, ldq), dtype=torch.uint8, device=x.device)[:, :t]
+    s_t = _scales(c, (t + 127) // 128, x.device, k_major_scales)
+    st = _L().ds3_quant_act_128x1(x.data_ptr(), _dt(x), t, c, ldx, q_t.data_ptr(), ldq,
+                                 s_t.data_ptr(), s_t.stride(0), s_t.stride(1), _stream())
+    _check(st, "ds3_quant_act_128x1")
+    return q_t, s_t
+
+
+def ds3_quant_w_128x128(w: torch.Tensor):
+    """w [N][K] -> (codes uint8 [N][K], scales FP32 [ceil(N/128)][ceil(K/128)])."""
+    n, k, ldw = _rows2d(w, "w")
+    q = torch.empty((n, k), dtype=torch.uint8, device=w.device)
+    s = torch.empty(((n + 127) // 128, (k + 127) // 128), dtype=torch.float32, device=w.device)
+    st = _L().ds3_quant_w_128x128(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), k, s.data_ptr(), _stream())
+    _check(st, "ds3_quant_w_128x128")
+    return q, s
+
+
+def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=torch.bfloat16,
+                    c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1):
+    """C[M][N] (+)= block-scaled product of codes a [M][K] (scales sa, logical
+    [M][K/128]) and b [N][K] (scales sb: [ceil(N/128)][K/128], or [N][K/128]
+    when sb_mode is DS3_BSCALE_PER_ROW)."""
+    m, k, lda = _rows2d(a, "a")
+    n, kb_, ldb = _rows2d(b, "b")
+    if kb_ != k:
+        raise ValueError("a and b disagree on K")
+    if c is None:
+        c = torch.empty((m, n), dtype=out_dtype, device=a.device)
+    _, _, ldc = _rows2d(c, "c")
+    st = _L().ds3_gemm_fp8_bs_v(variant, m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1),
+                               b.data_ptr(), ldb, sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode,
+                               c.data_ptr(), _dt(c), ldc, int(accumulate), None, 0, _stream())
+    _check(st, "ds3_gemm_fp8_bs")
+    return c
+
+
+def ds3_grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat16,
+                            c: torch.Tensor | None = None, variant: int = -1):
+    """Per expert g: rows [off[g], off[g+1]) of a times b[g] ([G][N][K] codes,
+    sb [G][ceil(N/128)][K/128]).  group_offsets: int32 device tensor of G+1."""
+    m, k, lda = _rows2d(a, "a")
+    g, n, kk = b.shape
+    if kk != k or not b.is_contiguous() or not sb.is_contiguous():
+        raise ValueError("b must be contiguous [G][N][K] and sb contiguous")
+    if group_offsets.dtype != torch.int32 or group_offsets.numel() != g + 1:
+        raise ValueError("group_offsets must be int32 of length G+1")
+    if c is None:
+        c = torch.empty((m, n), dtype=out_dtype, device=a.device)
+    _, _, ldc = _rows2d(c, "c")
+    st = _L().ds3_grouped_gemm_fp8_bs_v(variant, g, group_offsets.data_ptr(), m, n, k, a.data_ptr(), lda,
+                                       sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), k, sb.data_ptr(),
+                                       c.data_ptr(), _dt(c), ldc, None, 0, _stream())
+    _check(st, "ds3_grouped_gemm_fp8_bs")
+    return c
+
+
+def ds3_swiglu(h: torch.Tensor):
+    """h [rows][2*inter] BF16 (gate | up) -> silu(gate) * up, BF16 [rows][inter]."""
+    rows, two_i, ldh = _rows2d(h, "h")
+    if h.dtype != torch.bfloat16 or two_i % 2:
+        raise TypeError("h must be BF16 with an even number of columns")
+    out = torch.empty((rows, two_i // 2), dtype=torch.bfloat16, device=h.device)
+    st = _L().ds3_swiglu(h.data_ptr(), rows, two_i // 2, ldh, out.data_ptr(), two_i // 2, _stream())
+    _check(st, "ds3_swiglu")
+    return out
+
+
+def ds3_gemm_num_variants() -> int:
+    return int(_L().ds3_gemm_num_variants())
+
+
+def ds3_gemm_workspace_bytes(m: int, n: int, k: int) -> int:
+    return int(_L().ds3_gemm_workspace_bytes(m, n, k))

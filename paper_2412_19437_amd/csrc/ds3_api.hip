@@ -1,0 +1,157 @@
+// The C ABI of libds3: argument checking on the host, then a kernel launch.
+// No entry point allocates, synchronises or touches device data on the host.
+#include "ds3_internal.h"
+
+namespace ds3 { int gemm_num_variants(); }
+using namespace ds3;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t esize(ds3_dtype t) { return t == DS3_BF16 ? 2 : 4; }
+inline bool dtype_ok(ds3_dtype t) { return t == DS3_BF16 || t == DS3_F32; }
+constexpr int64_t kMaxDim = (1ll << 31) - 1;
+
+ds3_status check_quant(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, const void* q,
+                       int64_t ldq_min, int64_t ldq, const void* s) {
+    if (!dtype_ok(xt)) return DS3_ERR_DTYPE;
+    if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return DS3_OK;
+    if (!x || !q || !s) return DS3_ERR_NULL;
+    if (ldx < cols || ldq < ldq_min) return DS3_ERR_SHAPE;
+    if (rows > kMaxDim || cols > kMaxDim) return DS3_ERR_UNSUPPORTED;
+    const int64_t es = esize(xt);
+    if (!aligned16(x) || !aligned16(q) || (ldx * es) % 16 || ldq % 16 || (cols * es) % 16) return DS3_ERR_ALIGN;
+    return DS3_OK;
+}
+
+ds3_status gemm_common(int variant, int32_t G, const int32_t* offs, int64_t M, int64_t N, int64_t K, const uint8_t* a,
+                       int64_t lda, const float* sa, int64_t sar, int64_t sak, const uint8_t* b, int64_t ldb,
+                       const float* sb, int64_t sbr, int64_t sbk, ds3_bscale mode, void* c, ds3_dtype ct, int64_t ldc,
+                       int accumulate, void* stream) {
+    if (!dtype_ok(ct)) return DS3_ERR_DTYPE;
+    if (mode != DS3_BSCALE_128x128 && mode != DS3_BSCALE_PER_ROW) return DS3_ERR_DTYPE;
+    if (accumulate && ct != DS3_F32) return DS3_ERR_DTYPE;
+    if (M < 0 || N < 0 || K < 0 || G < 0) return DS3_ERR_SHAPE;
+    if (K % 128) return DS3_ERR_SHAPE;
+    if (variant < -1 || variant >= gemm_num_variants()) return DS3_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return DS3_OK;
+    if (K == 0) return accumulate ? DS3_OK : DS3_ERR_SHAPE;   // an empty sum cannot overwrite C without a kernel
+    if (!a || !b || !sa || !sb || !c) return DS3_ERR_NULL;
+    if (G > 0 && !offs) return DS3_ERR_NULL;
+    if (lda < K || ldb < K || ldc < N) return DS3_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || G > 65536) return DS3_ERR_UNSUPPORTED;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c) || lda % 16 || ldb % 16 || ldc % 4) return DS3_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DS3_ERR_ALIGN;
+    GemmParams p{};
+    p.a = a; p.b = b; p.sa = sa; p.sb = sb; p.c = c;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.sar = sar; p.sak = sak; p.sbr = sbr; p.sbk = sbk;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.G = G;
+    p.group_offsets = offs;
+    p.b_group_stride = N * ldb;
+    p.sb_group_stride = ((N + 127) / 128) * (K / 128);
+    p.accumulate = accumulate;
+    return launch_gemm(p, ct, mode, variant, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+ds3_status ds3_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                               int64_t ldq, float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    const ds3_status st = check_quant(x, xt, rows, cols, ldx, q, cols, ldq, s);
+    if (st != DS3_OK || rows == 0 || cols == 0) return st;
+    return launch_quant_act_1x128(x, xt, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb,
+                                  static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q_t,
+                               int64_t ldq, float* s_t, int64_t s_stride_col, int64_t s_stride_tb, void* stream) {
+    const ds3_status st = check_quant(x, xt, rows, cols, ldx, q_t, rows, ldq, s_t);
+    if (st != DS3_OK || rows == 0 || cols == 0) return st;
+    if ((rows + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_act_128x1(x, xt, rows, cols, ldx, q_t, ldq, s_t, s_stride_col, s_stride_tb,
+                                  static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q, int64_t ldq,
+                               float* s, void* stream) {
+    const ds3_status st = check_quant(w, wt, n, k, ldw, q, k, ldq, s);
+    if (st != DS3_OK || n == 0 || k == 0) return st;
+    if ((n + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_w_128x128(w, wt, n, k, ldw, q, ldq, s, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_gemm_fp8_bs_v(int variant, int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda,
+                             const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b,
+                             int64_t ldb, const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb,
+                             ds3_bscale sb_mode, void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return gemm_common(variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
+                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, stream);
+}
+
+ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                           int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
+                           const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode, void* c,
+                           ds3_dtype ct, int64_t ldc, int accumulate, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    return ds3_gemm_fp8_bs_v(-1, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb, sb_stride_row,
+                             sb_stride_kb, sb_mode, c, ct, ldc, accumulate, workspace, workspace_bytes, stream);
+}
+
+ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                     int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                                     int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
+                                     const float* sb, void* c, ds3_dtype ct, int64_t ldc, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (G < 0) return DS3_ERR_SHAPE;
+    if (G == 0) return DS3_OK;
+    if (N > 0 && K > 0 && (int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
+    return gemm_common(variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
+                       sb, K / 128, 1, DS3_BSCALE_128x128, c, ct, ldc, 0, stream);
+}
+
+ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t N, int64_t K,
+                                   const uint8_t* a, int64_t lda, const float* sa, int64_t sa_stride_row,
+                                   int64_t sa_stride_kb, const uint8_t* b, int64_t ldb, const float* sb, void* c,
+                                   ds3_dtype ct, int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
+    return ds3_grouped_gemm_fp8_bs_v(-1, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb,
+                                     b, ldb, sb, c, ct, ldc, workspace, workspace_bytes, stream);
+}
+
+int ds3_gemm_num_variants(void) { return gemm_num_variants(); }
+
+size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    (void)M; (void)N; (void)K;
+    return 0;
+}
+
+ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo, void* stream) {
+    if (rows < 0 || inter < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || inter == 0) return DS3_OK;
+    if (!h || !out) return DS3_ERR_NULL;
+    if (ldh < 2 * inter || ldo < inter) return DS3_ERR_SHAPE;
+    if (!aligned16(h) || !aligned16(out) || inter % 8 || ldh % 8 || ldo % 8) return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || inter > kMaxDim) return DS3_ERR_UNSUPPORTED;
+    return launch_swiglu(h, rows, inter, ldh, out, ldo, static_cast<hipStream_t>(stream));
+}
+
+const char* ds3_status_string(ds3_status st) {
+    switch (st) {
+        case DS3_OK: return "ok";
+        case DS3_ERR_NULL: return "null pointer";
+        case DS3_ERR_SHAPE: return "bad shape or leading dimension";
+        case DS3_ERR_ALIGN: return "pointer, leading dimension or column count not 16-byte aligned";
+        case DS3_ERR_DTYPE: return "bad dtype / mode";
+        case DS3_ERR_UNSUPPORTED: return "size or variant not supported";
+        case DS3_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Device-side helpers shared by the gfx950 kernels of this library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ds3 {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float as_f32(unsigned int u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned int as_u32(float f) { return __builtin_bit_cast(unsigned int, f); }
+
+// BF16 -> FP32 widening is a 16-bit shift; a 32-bit word holds two elements,
+// the lower-addressed one in the low half.
+__device__ __forceinline__ float bf16_lo(unsigned int w) { return as_f32(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned int w) { return as_f32(w & 0xffff0000u); }
+
+// FP32 -> BF16, round to nearest even (finite inputs).
+__device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
+    unsigned int u = as_u32(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+}
+
+// Max over the 16 lanes of a DPP row; every lane of the row gets the result.
+// Operates on the bit patterns of non-negative finite floats, for which the
+// unsigned integer order equals the floating-point order (no NaN handling,
+// no canonicalisation instructions).
+template <int CTRL>
+__device__ __forceinline__ unsigned int dpp_u32(unsigned int v) {
+    return (unsigned int)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ unsigned int umax(unsigned int a, unsigned int b) { return a > b ? a : b; }
+__device__ __forceinline__ unsigned int row16_max_bits(unsigned int v) {
+    v = umax(v, dpp_u32<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = umax(v, dpp_u32<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = umax(v, dpp_u32<0x141>(v));  // row_half_mirror: quads 0<->1, 2<->3
+    v = umax(v, dpp_u32<0x140>(v));  // row_mirror: halves
+    return v;
+}
+
+// The two per-group factors of the quantisation contract: the stored scale
+// s = amax / 448 and the multiplier r = 448 / amax, both correctly rounded
+// FP32 divisions; an all-zero group gives s = 1, r = 0.
+struct GroupScale { float s, r; };
+__device__ __forceinline__ GroupScale group_scale(float amax) {
+    GroupScale g;
+    if (amax == 0.0f) { g.s = 1.0f; g.r = 0.0f; }
+    else { g.s = amax / 448.0f; g.r = 448.0f / amax; }
+    return g;
+}
+
+// Four FP32 values -> four E4M3 codes in one 32-bit word (lowest address in
+// the low byte); the hardware conversion rounds to nearest even.
+__device__ __forceinline__ unsigned int cvt4_e4m3(float a, float b, float c, float d) {
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+    return (unsigned int)w;
+}
+
+}  // namespace ds3

@@ -1,0 +1,353 @@
+// Block-scaled FP8 GEMM for gfx950, dense and grouped over MoE experts --
+// Section 3.3.2 "Increasing Accumulation Precision" of the DeepSeek-V3 report:
+// per-group scales along K are multiplied into every 128-long partial sum and
+// the sums are accumulated in FP32.
+//
+// Design (not the report's Hopper scheme): one v_mfma_f32_16x16x128_f8f6f4
+// spans exactly one N_C = 128 interval, so each MFMA is issued with a zero
+// accumulator and its four results per lane are folded into the FP32
+// accumulators with one v_fma each.  The weight tile is the MFMA row operand
+// and the activation tile the column operand: a lane then owns ONE activation
+// row and four consecutive weight rows, so the scale product
+// sa(m,kb) * sb(n/128,kb) is a single per-lane value per activation fragment.
+//
+// Data path: 128-byte K-rows of both operands go global -> LDS with 128-bit
+// accesses (optionally straight into LDS, bypassing registers), two stages;
+// LDS rows are 128 bytes with the eight 16-byte chunks XOR-swizzled by
+// (row ^ row>>3) & 7 so that the 16 rows x 2 chunks a fragment read touches
+// fall into distinct banks.  Workgroup ids are remapped so that each XCD (one
+// L2 each, workgroups are dealt round-robin to the 8 XCDs) walks a compact
+// panel of output tiles.
+#include <type_traits>
+
+#include "ds3_dev.h"
+#include "ds3_internal.h"
+
+namespace ds3 {
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+template <int BN_, int BM_, int WN_, int WM_, bool DIRECT_>
+struct Cfg {
+    static constexpr int BN = BN_, BM = BM_, WN = WN_, WM = WM_;
+    static constexpr bool DIRECT = DIRECT_;
+    static constexpr int NT = 64 * WN * WM;
+    static constexpr int TN = BN / WN, TM = BM / WM;   // wave tile
+    static constexpr int FN = TN / 16, FM = TM / 16;   // 16-row fragments per wave
+    static constexpr int ROWS = BN + BM;
+    static constexpr int STAGE = ROWS * 128;           // bytes of codes per K-step
+    static constexpr int RPI = NT / 8;                 // tile rows one load instruction of the workgroup covers
+    static constexpr int LPT = ROWS / RPI;             // 16-byte loads per thread per K-step
+    static constexpr int LDS_BYTES = 2 * STAGE + 4 * NT * 4;     // codes + [2][NT] sa + [2][NT] per-row sb
+    static_assert(ROWS % RPI == 0 && BN % RPI == 0 && RPI % 16 == 0, "load mapping");
+    static_assert(BM <= NT && BN <= NT, "scale staging uses one thread per row");
+    static_assert(TN <= 128 && 128 % TN == 0, "one weight-scale block per wave");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+__device__ __forceinline__ int swz_key(int row) { return (row ^ (row >> 3)) & 7; }
+
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
+__global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
+    constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE;
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[C::LDS_BYTES];
+    float* const sa_s = reinterpret_cast<float*>(smem + 2 * STAGE);            // [2][NT], first BM used
+    float* const sbrow_s = sa_s + 2 * NT;                                      // [2][NT], first BN used (per-row mode)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave % C::WN, wm = wave / C::WN;
+    const int l16 = lane & 15, g4 = lane >> 4;
+
+    // ---- which output tile ------------------------------------------------------
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int per_xcd = (ntiles + 7) >> 3;
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= ntiles) return;
+    int m0, m_end, n0, grp = 0;
+    if constexpr (!GROUPED) {
+        constexpr int PM = 4;                          // tiles of M per panel
+        const int panel = PM * p.tiles_n;
+        const int pi = t / panel, r = t - pi * panel;
+        const int pm = min(PM, p.tiles_m - pi * PM);
+        m0 = (pi * PM + r % pm) * BM;
+        n0 = (r / pm) * BN;
+        m_end = p.M;
+    } else {
+        const int mt = t / p.tiles_n;
+        n0 = (t - mt * p.tiles_n) * BN;
+        int cum = 0, lo = p.group_offsets[0];
+        m0 = -1; m_end = 0;
+        for (int g = 0; g < p.G; ++g) {
+            const int hi = p.group_offsets[g + 1];
+            const int nt_g = (hi - lo + BM - 1) / BM;
+            if (m0 < 0 && mt < cum + nt_g) { grp = g; m0 = lo + (mt - cum) * BM; m_end = hi; }
+            cum += nt_g;
+            lo = hi;
+        }
+        if (m0 < 0) return;
+        m_end = min(m_end, p.M);
+    }
+    const int m_rows = min(m_end - m0, BM);            // valid rows of this tile (>= 1)
+    const int n_rows = min(p.N - n0, BN);
+    const int KB = p.K >> 7;
+
+    const uint8_t* a_tile = p.a + (int64_t)m0 * p.lda;
+    const uint8_t* b_tile = p.b + (int64_t)grp * p.b_group_stride + (int64_t)n0 * p.ldb;
+    // Buffer descriptors bound to the valid bytes of the tile: rows past the
+    // end of the matrix (or of the expert's group) read as zero.
+    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)a_tile, 0, (int)((int64_t)(m_rows - 1) * p.lda + p.K), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)b_tile, 0, (int)((int64_t)(n_rows - 1) * p.ldb + p.K), 0x00020000);
+
+    // load mapping: this thread moves chunk position (tid & 7) of tile row i*RPI + (tid >> 3)
+    const int lrow = tid >> 3;
+    const int gchunk = (tid & 7) ^ swz_key(lrow);      // which 16 bytes of the K-row land there
+    const int voff_b = lrow * (int)p.ldb + gchunk * 16;
+    const int voff_a = lrow * (int)p.lda + gchunk * 16;
+    const int step_b = C::RPI * (int)p.ldb, step_a = C::RPI * (int)p.lda;
+
+    // fragment read offsets inside a 16-row group: lane reads chunks 2*g4 and 2*g4+1 of row l16
+    const int key = swz_key(l16);
+    const int foff0 = l16 * 128 + (((2 * g4) ^ key) << 4);
+    const int foff1 = l16 * 128 + (((2 * g4 + 1) ^ key) << 4);
+    const int p_base = wn * C::TN * 128;               // weight fragments of this wave
+    const int q_base = (BN + wm * C::TM) * 128;        // activation fragments of this wave
+
+    // scales
+    const float* sa_tile = p.sa + (int64_t)m0 * p.sar;
+    const float* sb_blk;                               // block mode: this wave's block row; row mode: tile base
+    if constexpr (ROWSB) {
+        sb_blk = p.sb + (int64_t)n0 * p.sbr;
+    } else {
+        const int nblocks = (p.N + 127) >> 7;
+        const int nb = min((n0 + wn * C::TN) >> 7, nblocks - 1);
+        sb_blk = p.sb + (int64_t)grp * p.sb_group_stride + (int64_t)nb * p.sbr;
+    }
+
+    u32x4 stg[C::DIRECT ? 1 : C::LPT];
+    float sa_reg = 0.f, sbrow_reg = 0.f;
+    // Every thread stages one activation scale (and one per-row weight scale);
+    // threads past the valid rows re-read the last valid row, whose partial
+    // sums are zero because its codes were read as zero.
+    const float* sa_thr = sa_tile + (int64_t)min(tid, m_rows - 1) * p.sar;
+    const float* sbrow_thr = ROWSB ? sb_blk + (int64_t)min(tid, n_rows - 1) * p.sbr : nullptr;
+
+    auto issue_loads = [&](int kb, int stage) {
+        const int koff = kb << 7;
+#pragma unroll
+        for (int i = 0; i < C::LPT; ++i) {
+            const bool is_b = i * C::RPI < BN;
+            const int ii = is_b ? i : i - BN / C::RPI;
+            const int voff = is_b ? voff_b : voff_a;
+            const int soff = koff + ii * (is_b ? step_b : step_a);
+            if constexpr (C::DIRECT) {
+                uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? rs_b : rs_a, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
+            } else {
+                stg[i] = __builtin_amdgcn_raw_buffer_load_b128(is_b ? rs_b : rs_a, voff, soff, 0);
+            }
+        }
+        sa_reg = sa_thr[(int64_t)kb * p.sak];
+        if constexpr (ROWSB) sbrow_reg = sbrow_thr[(int64_t)kb * p.sbk];
+    };
+    auto commit_loads = [&](int stage) {
+        if constexpr (!C::DIRECT) {
+#pragma unroll
+            for (int i = 0; i < C::LPT; ++i)
+                *reinterpret_cast<u32x4*>(smem + stage * STAGE + (i * NT + tid) * 16) = stg[i];
+        }
+        sa_s[stage * NT + tid] = sa_reg;
+        if constexpr (ROWSB) sbrow_s[stage * NT + tid] = sbrow_reg;
+    };
+
+    f32x4 acc[FN][FM];
+#pragma unroll
+    for (int i = 0; i < FN; ++i)
+#pragma unroll
+        for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto load_frag = [&](const uint8_t* base) -> i32x8 {
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(base + foff0);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(base + foff1);
+        return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+
+    // One K-step of this wave on LDS stage `stage`.  The instruction order is
+    // pinned by hand: the MFMA of sub-tile s is issued, then the four FMAs that
+    // fold sub-tile s-D into the accumulators, so the vector ALU works in the
+    // shadow of the matrix pipe.  The empty asm statements only tie values to
+    // program points (they emit nothing): without them the compiler gathers all
+    // MFMAs first and all FMAs last.
+    constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
+    auto compute = [&](int stage, float sbv) {
+        const uint8_t* st = smem + stage * STAGE;
+        float tj[FM];
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const float sav = sa_s[stage * NT + wm * C::TM + j * 16 + l16];
+            tj[j] = ROWSB ? sav : sav * sbv;
+        }
+        f32x4 un[FN];
+        if constexpr (ROWSB) {
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+                un[i] = *reinterpret_cast<const f32x4*>(sbrow_s + stage * NT + wn * C::TN + i * 16 + g4 * 4);
+        }
+        i32x8 pf[FN];
+#pragma unroll
+        for (int i = 0; i < FN; ++i) pf[i] = load_frag(st + p_base + i * 2048);
+        i32x8 qf[2];
+        qf[0] = load_frag(st + q_base);
+        f32x4 part[D + 1];
+#pragma unroll
+        for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < FN * FM + D; ++s) {
+            if (s < FN * FM) {
+                const int j = s / FN, i = s % FN;
+                if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
+                part[s % (D + 1)] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                    pf[i], qf[j & 1], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+            }
+            if (s >= D) {
+                const int ps = s - D, j = ps / FN, i = ps % FN;
+                // the MFMA just issued comes before the FMAs of sub-tile ps
+                if (s < FN * FM) asm volatile("" : "+v"(part[s % (D + 1)]), "+v"(part[ps % (D + 1)]));
+                const f32x4 pr = part[ps % (D + 1)];
+                f32x4 a = acc[i][j];
+                if constexpr (ROWSB) {
+                    a.x = __builtin_fmaf(pr.x, tj[j] * un[i].x, a.x);
+                    a.y = __builtin_fmaf(pr.y, tj[j] * un[i].y, a.y);
+                    a.z = __builtin_fmaf(pr.z, tj[j] * un[i].z, a.z);
+                    a.w = __builtin_fmaf(pr.w, tj[j] * un[i].w, a.w);
+                } else {
+                    a.x = __builtin_fmaf(pr.x, tj[j], a.x);
+                    a.y = __builtin_fmaf(pr.y, tj[j], a.y);
+                    a.z = __builtin_fmaf(pr.z, tj[j], a.z);
+                    a.w = __builtin_fmaf(pr.w, tj[j], a.w);
+                }
+                asm volatile("" : "+v"(a));              // the four FMAs are done by here
+                acc[i][j] = a;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- main loop: two LDS stages, loads for K-step kb+1 fly during compute of kb ----
+    // step(kb, S, more): compute K-step kb from stage S; when `more`, fetch K-step kb+1 into stage S^1.
+    float sb_next = ROWSB ? 1.f : sb_blk[0];
+    auto step = [&](int kb, int stage, auto more_tag) {
+        constexpr bool more = decltype(more_tag)::value;
+        const float sbv = sb_next;
+        if constexpr (more) {
+            issue_loads(kb + 1, stage ^ 1);
+            if constexpr (!ROWSB) sb_next = sb_blk[(int64_t)(kb + 1) * p.sbk];
+        }
+        compute(stage, sbv);
+        if constexpr (more) commit_loads(stage ^ 1);
+        __syncthreads();
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    issue_loads(0, 0);
+    commit_loads(0);
+    __syncthreads();
+    int kb = 0;
+    for (; kb + 2 < KB; kb += 2) {
+        step(kb, 0, yes{});
+        step(kb + 1, 1, yes{});
+    }
+    // one or two K-steps remain
+    if (kb + 2 == KB) {
+        step(kb, 0, yes{});
+        step(kb + 1, 1, no{});
+    } else {
+        step(kb, 0, no{});
+    }
+
+    // ---- epilogue: lane owns activation row m and, per weight fragment, 4 consecutive n ----
+    constexpr int ESZ = OUT_BF16 ? 2 : 4;
+    uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
+#pragma unroll
+    for (int j = 0; j < FM; ++j) {
+        const int ml = wm * C::TM + j * 16 + l16;
+        if (ml >= m_rows) continue;
+        uint8_t* crow = c_base + ((int64_t)(m0 + ml) * p.ldc + n0) * ESZ;
+#pragma unroll
+        for (int i = 0; i < FN; ++i) {
+            const int nl = wn * C::TN + i * 16 + g4 * 4;
+            if (nl >= n_rows) continue;
+            const f32x4 v = acc[i][j];
+            if (nl + 4 <= n_rows) {
+                if constexpr (OUT_BF16) {
+                    *reinterpret_cast<u32x2*>(crow + nl * 2) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+                } else {
+                    f32x4* dst = reinterpret_cast<f32x4*>(crow + nl * 4);
+                    f32x4 o = v;
+                    if (p.accumulate) { const f32x4 old = *dst; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
+                    *dst = o;
+                }
+            } else {
+                const float e[4] = {v.x, v.y, v.z, v.w};
+                for (int q = 0; q < 4 && nl + q < n_rows; ++q) {
+                    if constexpr (OUT_BF16) {
+                        reinterpret_cast<uint16_t*>(crow)[nl + q] = (uint16_t)f32_to_bf16_rne(e[q]);
+                    } else {
+                        float* dst = reinterpret_cast<float*>(crow) + nl + q;
+                        *dst = p.accumulate ? *dst + e[q] : e[q];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---- host side -------------------------------------------------------------------
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
+static ds3_status launch_one(GemmParams p, hipStream_t st) {
+    if (GROUPED) p.tiles_m = (p.M + C::BM - 1) / C::BM + p.G;
+    else p.tiles_m = (p.M + C::BM - 1) / C::BM;
+    p.tiles_n = (p.N + C::BN - 1) / C::BN;
+    const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
+    if (ntiles <= 0) return DS3_OK;
+    if (ntiles > (1 << 28)) return DS3_ERR_UNSUPPORTED;
+    // 32-bit byte offsets inside one tile's rows
+    if ((int64_t)C::BN * p.ldb + p.K >= (1ll << 31) || (int64_t)C::BM * p.lda + p.K >= (1ll << 31))
+        return DS3_ERR_UNSUPPORTED;
+    const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
+    gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
+    return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
+}
+
+template <class C>
+static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, hipStream_t st) {
+    const bool bf16 = ct == DS3_BF16;
+    if (p.G > 0) return bf16 ? launch_one<C, false, true, true>(p, st) : launch_one<C, false, false, true>(p, st);
+    if (mode == DS3_BSCALE_PER_ROW)
+        return bf16 ? launch_one<C, true, true, false>(p, st) : launch_one<C, true, false, false>(p, st);
+    return bf16 ? launch_one<C, false, true, false>(p, st) : launch_one<C, false, false, false>(p, st);
+}
+
+int gemm_num_variants() { return 6; }
+
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
+    if (variant < 0) {
+        // default choice by shape: grouped problems and small-M problems take the narrower M tile
+        variant = (p.G > 0) ? 2 : 0;
+    }
+    switch (variant) {
+        case 0: return launch_cfg<Cfg<256, 256, 4, 2, false>>(p, ct, mode, st);
+        case 1: return launch_cfg<Cfg<256, 256, 4, 2, true>>(p, ct, mode, st);
+        case 2: return launch_cfg<Cfg<256, 128, 4, 2, false>>(p, ct, mode, st);
+        case 3: return launch_cfg<Cfg<256, 128, 4, 2, true>>(p, ct, mode, st);
+        case 4: return launch_cfg<Cfg<128, 128, 2, 2, false>>(p, ct, mode, st);
+        case 5: return launch_cfg<Cfg<128, 128, 2, 2, true>>(p, ct, mode, st);
+        default: return DS3_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace ds3

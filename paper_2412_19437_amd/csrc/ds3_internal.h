@@ -1,0 +1,41 @@
+// Host-side declarations shared by the translation units of libds3.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ds3.h"
+
+namespace ds3 {
+
+ds3_status launch_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, hipStream_t st);
+ds3_status launch_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* qt,
+                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, hipStream_t st);
+ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                  int64_t ldq, float* s, hipStream_t st);
+ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo,
+                         hipStream_t st);
+
+// One description for the dense and the grouped GEMM.  Dense: G == 0.
+struct GemmParams {
+    const uint8_t* a;      // [M][lda] activation-side codes
+    const uint8_t* b;      // [N][ldb] weight-side codes (grouped: [G][N][ldb])
+    const float* sa;
+    const float* sb;
+    void* c;
+    int64_t lda, ldb, ldc;
+    int64_t sar, sak;      // sa strides: row, K-block
+    int64_t sbr, sbk;      // sb strides: row (block row or row), K-block
+    int64_t b_group_stride;   // bytes between experts in b
+    int64_t sb_group_stride;  // floats between experts in sb
+    const int32_t* group_offsets;
+    int M, N, K;           // grouped: M = total rows
+    int G;
+    int tiles_m, tiles_n;  // grouped: tiles_m is the upper bound ceil(M/BM) + G
+    int accumulate;
+};
+
+// variant: which tile configuration to run (see ds3_gemm.hip); -1 = choose by shape.
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st);
+
+}  // namespace ds3

@@ -1,0 +1,327 @@
+// Online E4M3 quantizers for gfx950: 1x128 activation tiles, 128x128 weight
+// blocks and 128x1 (token-axis) tiles -- Section 3.3.2 "Fine-Grained
+// Quantization" / "Online Quantization" and Section 3.3.3 "Low-Precision
+// Activation" (1) of the DeepSeek-V3 report.  All three are single-pass HBM
+// scans: every input element is read once with 128-bit loads, the max-abs is
+// reduced in registers / across lanes, and codes plus FP32 scales are written
+// from the same registers.
+#include "ds3_dev.h"
+#include "ds3_internal.h"
+
+namespace ds3 {
+
+// ----- element traits: how many elements one 16-byte load carries --------------
+struct Bf16 { static constexpr int EPL = 8; };   // elements per 128-bit load
+struct F32  { static constexpr int EPL = 4; };
+
+// Widen the EPL elements of one 16-byte granule to FP32.
+template <typename T> __device__ __forceinline__ void widen(const u32x4& g, float* v);
+template <> __device__ __forceinline__ void widen<Bf16>(const u32x4& g, float* v) {
+    v[0] = bf16_lo(g.x); v[1] = bf16_hi(g.x); v[2] = bf16_lo(g.y); v[3] = bf16_hi(g.y);
+    v[4] = bf16_lo(g.z); v[5] = bf16_hi(g.z); v[6] = bf16_lo(g.w); v[7] = bf16_hi(g.w);
+}
+template <> __device__ __forceinline__ void widen<F32>(const u32x4& g, float* v) {
+    v[0] = as_f32(g.x); v[1] = as_f32(g.y); v[2] = as_f32(g.z); v[3] = as_f32(g.w);
+}
+
+// max |element| of one granule, as the bit pattern of a non-negative float.
+template <typename T> __device__ __forceinline__ unsigned int granule_amax_bits(const u32x4& g);
+template <> __device__ __forceinline__ unsigned int granule_amax_bits<Bf16>(const u32x4& g) {
+    unsigned int m = 0;
+    const unsigned int w[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        m = umax(m, w[i] & 0x7fff0000u);
+        m = umax(m, (w[i] << 16) & 0x7fff0000u);
+    }
+    return m;
+}
+template <> __device__ __forceinline__ unsigned int granule_amax_bits<F32>(const u32x4& g) {
+    return umax(umax(g.x & 0x7fffffffu, g.y & 0x7fffffffu), umax(g.z & 0x7fffffffu, g.w & 0x7fffffffu));
+}
+
+// =============================================================================
+// 1x128: one 16-lane DPP row per tile.  A workgroup is 16 rows of the matrix
+// (one per DPP row of its 4 waves) by TPG consecutive tiles, so each lane has
+// TPG independent 128-bit loads in flight and the 16 scales of one K-block
+// land in 64 contiguous bytes of a K-block-major scale array.
+// =============================================================================
+template <typename T, int TPG>
+__global__ __launch_bounds__(256) void quant_act_1x128_kernel(
+    const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes,
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t ssr, int64_t ssk) {
+    constexpr int EPL = T::EPL;
+    constexpr int GPT = 8 / EPL;                  // granules per lane per tile (16 lanes x 8 elements)
+    constexpr int ESZ = 16 / EPL;                 // bytes per element
+    const int lane16 = threadIdx.x & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (row >= rows) return;                      // a whole DPP row leaves together
+    const int64_t kb0 = (int64_t)blockIdx.y * TPG;
+    const int64_t nkb = (cols + 127) >> 7;
+    const uint8_t* xr = x + row * ldx_bytes;
+
+    u32x4 g[TPG][GPT];
+    bool ok[TPG][GPT];
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+#pragma unroll
+        for (int h = 0; h < GPT; ++h) {
+            // granule h of the lane covers elements [h*64 + lane16*EPL, +EPL) of the tile when GPT == 2
+            const int64_t col = (kb0 + t) * 128 + h * (128 / GPT) + lane16 * EPL;
+            ok[t][h] = col < cols;
+            g[t][h] = u32x4{0u, 0u, 0u, 0u};
+            if (ok[t][h]) g[t][h] = *reinterpret_cast<const u32x4*>(xr + col * ESZ);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+        if (kb0 + t >= nkb) break;
+        unsigned int m = 0;
+#pragma unroll
+        for (int h = 0; h < GPT; ++h) m = umax(m, granule_amax_bits<T>(g[t][h]));
+        m = row16_max_bits(m);
+        const GroupScale gs = group_scale(as_f32(m));
+        if (lane16 == 0) s[row * ssr + (kb0 + t) * ssk] = gs.s;
+#pragma unroll
+        for (int h = 0; h < GPT; ++h) {
+            float v[EPL];
+            widen<T>(g[t][h], v);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) v[i] = v[i] * gs.r;
+            const int64_t col = (kb0 + t) * 128 + h * (128 / GPT) + lane16 * EPL;
+            uint8_t* dst = q + row * ldq + col;
+            if (ok[t][h]) {
+                if constexpr (EPL == 8) {
+                    u32x2 w = {cvt4_e4m3(v[0], v[1], v[2], v[3]), cvt4_e4m3(v[4], v[5], v[6], v[7])};
+                    *reinterpret_cast<u32x2*>(dst) = w;
+                } else {
+                    *reinterpret_cast<unsigned int*>(dst) = cvt4_e4m3(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+    }
+}
+
+// =============================================================================
+// 128x128: one workgroup per block.  The whole block (32 KiB BF16 / 64 KiB
+// FP32) is held in registers between the max-abs pass and the cast, so HBM is
+// read exactly once.
+// =============================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void quant_w_128x128_kernel(
+    const uint8_t* __restrict__ w, int64_t n, int64_t k, int64_t ldw_bytes,
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t nkb) {
+    constexpr int EPL = T::EPL;
+    constexpr int ESZ = 16 / EPL;
+    constexpr int LPR = 128 / EPL;                // lanes per block row
+    constexpr int RPP = 256 / LPR;                // rows per pass
+    constexpr int NP = 128 / RPP;                 // passes
+    __shared__ unsigned int red[16];
+    const int64_t kb = blockIdx.x, nb = blockIdx.y;
+    const int lc = threadIdx.x % LPR, lr = threadIdx.x / LPR;
+    const int64_t col = kb * 128 + lc * EPL;
+    const bool col_ok = col < k;
+
+    u32x4 g[NP];
+    unsigned int m = 0;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int64_t row = nb * 128 + p * RPP + lr;
+        g[p] = u32x4{0u, 0u, 0u, 0u};
+        if (col_ok && row < n) g[p] = *reinterpret_cast<const u32x4*>(w + row * ldw_bytes + col * ESZ);
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) m = umax(m, granule_amax_bits<T>(g[p]));
+    m = row16_max_bits(m);
+    if ((threadIdx.x & 15) == 0) red[threadIdx.x >> 4] = m;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m = umax(m, red[i]);
+    const GroupScale gs = group_scale(as_f32(m));
+    if (threadIdx.x == 0) s[nb * nkb + kb] = gs.s;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int64_t row = nb * 128 + p * RPP + lr;
+        float v[EPL];
+        widen<T>(g[p], v);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) v[i] = v[i] * gs.r;
+        if (col_ok && row < n) {
+            uint8_t* dst = q + row * ldq + col;
+            if constexpr (EPL == 8) {
+                u32x2 o = {cvt4_e4m3(v[0], v[1], v[2], v[3]), cvt4_e4m3(v[4], v[5], v[6], v[7])};
+                *reinterpret_cast<u32x2*>(dst) = o;
+            } else {
+                *reinterpret_cast<unsigned int*>(dst) = cvt4_e4m3(v[0], v[1], v[2], v[3]);
+            }
+        }
+    }
+}
+
+// =============================================================================
+// 128x1: a workgroup takes 128 tokens x 128 channels.  Each thread loads TPT
+// consecutive tokens of one 16-byte channel granule, so after the column
+// max-abs (registers, then LDS across the token slices) it owns TPT
+// consecutive codes of each of its channels; these go through an LDS tile
+// laid out [channel][token] and leave as 16-byte token-contiguous stores.
+// =============================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void quant_act_128x1_kernel(
+    const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes,
+    uint8_t* __restrict__ qt, int64_t ldq, float* __restrict__ st, int64_t ssc, int64_t sst) {
+    constexpr int EPL = T::EPL;
+    constexpr int ESZ = 16 / EPL;
+    constexpr int LPR = 128 / EPL;                // lanes across the 128 channels
+    constexpr int NSL = 256 / LPR;                // token slices (16 for BF16, 8 for FP32)
+    constexpr int TPT = 128 / NSL;                // consecutive tokens per thread (8 / 16)
+    constexpr int OST = 128 + 16;                 // LDS row stride of the [channel][token] tile
+    __shared__ unsigned int part[NSL][128];
+    __shared__ float rmul[128];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[128 * OST];
+
+    const int64_t c0 = (int64_t)blockIdx.x * 128, t0 = (int64_t)blockIdx.y * 128;
+    const int lc = threadIdx.x % LPR, sl = threadIdx.x / LPR;
+    const int64_t col = c0 + lc * EPL;
+    const bool col_ok = col < cols;
+
+    u32x4 g[TPT];
+#pragma unroll
+    for (int p = 0; p < TPT; ++p) {
+        const int64_t tok = t0 + sl * TPT + p;
+        g[p] = u32x4{0u, 0u, 0u, 0u};
+        if (col_ok && tok < rows) g[p] = *reinterpret_cast<const u32x4*>(x + tok * ldx_bytes + col * ESZ);
+    }
+    // per-channel max over this thread's tokens
+    unsigned int cm[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) cm[i] = 0;
+#pragma unroll
+    for (int p = 0; p < TPT; ++p) {
+        const unsigned int wds[4] = {g[p].x, g[p].y, g[p].z, g[p].w};
+        if constexpr (EPL == 8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cm[2 * i] = umax(cm[2 * i], (wds[i] << 16) & 0x7fff0000u);
+                cm[2 * i + 1] = umax(cm[2 * i + 1], wds[i] & 0x7fff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cm[i] = umax(cm[i], wds[i] & 0x7fffffffu);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) part[sl][lc * EPL + i] = cm[i];
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        unsigned int m = 0;
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) m = umax(m, part[j][threadIdx.x]);
+        const GroupScale gs = group_scale(as_f32(m));
+        rmul[threadIdx.x] = gs.r;
+        if (c0 + threadIdx.x < cols) st[(c0 + threadIdx.x) * ssc + (int64_t)blockIdx.y * sst] = gs.s;
+    }
+    __syncthreads();
+    // cast, and gather each channel's TPT consecutive tokens into the LDS tile
+    float r[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) r[i] = rmul[lc * EPL + i];
+    float y[TPT][EPL];
+#pragma unroll
+    for (int p = 0; p < TPT; ++p) {
+        widen<T>(g[p], y[p]);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) y[p][i] = y[p][i] * r[i];
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+        uint8_t* dst = tile + (lc * EPL + i) * OST + sl * TPT;
+#pragma unroll
+        for (int p = 0; p < TPT; p += 8) {
+            u32x2 o = {cvt4_e4m3(y[p][i], y[p + 1][i], y[p + 2][i], y[p + 3][i]),
+                       cvt4_e4m3(y[p + 4][i], y[p + 5][i], y[p + 6][i], y[p + 7][i])};
+            *reinterpret_cast<u32x2*>(dst + p) = o;
+        }
+    }
+    __syncthreads();
+    // 128 channels x 8 chunks of 16 tokens
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ch = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
+        const int64_t tok = t0 + chunk * 16;
+        if (c0 + ch >= cols || tok >= rows) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + ch * OST + chunk * 16);
+        uint8_t* dst = qt + (c0 + ch) * ldq + tok;
+        if (tok + 16 <= rows) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+            const unsigned int wds[4] = {v.x, v.y, v.z, v.w};
+            for (int b = 0; b < 16 && tok + b < rows; ++b) dst[b] = (uint8_t)(wds[b >> 2] >> (8 * (b & 3)));
+        }
+    }
+}
+
+// =============================================================================
+// SwiGLU between the two expert GEMMs: out = silu(gate) * up in FP32, BF16 out.
+// =============================================================================
+__global__ __launch_bounds__(256) void swiglu_kernel(const uint8_t* __restrict__ h, int64_t rows, int64_t inter,
+                                                     int64_t ldh_bytes, uint8_t* __restrict__ out, int64_t ldo_bytes) {
+    const int64_t gpr = inter >> 3;                                  // 8-element granules per row
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * gpr) return;
+    const int64_t row = idx / gpr, gi = idx - row * gpr;
+    const u32x4 gg = *reinterpret_cast<const u32x4*>(h + row * ldh_bytes + gi * 16);
+    const u32x4 uu = *reinterpret_cast<const u32x4*>(h + row * ldh_bytes + (inter + gi * 8) * 2);
+    float g[8], u[8], o[8];
+    widen<Bf16>(gg, g);
+    widen<Bf16>(uu, u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = g[i] / (1.0f + __expf(-g[i])) * u[i];
+    u32x4 w = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
+    *reinterpret_cast<u32x4*>(out + row * ldo_bytes + gi * 16) = w;
+}
+
+// ----- host launchers -----------------------------------------------------------
+static ds3_status launch_status() { return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH; }
+
+ds3_status launch_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, hipStream_t st) {
+    constexpr int TPG = 4;
+    const int64_t nkb = (cols + 127) / 128;
+    dim3 grid((unsigned)((rows + 15) / 16), (unsigned)((nkb + TPG - 1) / TPG));
+    if (xt == DS3_BF16)
+        quant_act_1x128_kernel<Bf16, TPG><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 2, q, ldq, s, ssr, ssk);
+    else
+        quant_act_1x128_kernel<F32, TPG><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 4, q, ldq, s, ssr, ssk);
+    return launch_status();
+}
+
+ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                  int64_t ldq, float* s, hipStream_t st) {
+    const int64_t nkb = (k + 127) / 128, nnb = (n + 127) / 128;
+    dim3 grid((unsigned)nkb, (unsigned)nnb);
+    if (wt == DS3_BF16)
+        quant_w_128x128_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 2, q, ldq, s, nkb);
+    else
+        quant_w_128x128_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 4, q, ldq, s, nkb);
+    return launch_status();
+}
+
+ds3_status launch_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* qt,
+                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, hipStream_t st) {
+    dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
+    if (xt == DS3_BF16)
+        quant_act_128x1_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 2, qt, ldq, s_t, ssc, sst);
+    else
+        quant_act_128x1_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 4, qt, ldq, s_t, ssc, sst);
+    return launch_status();
+}
+
+ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo,
+                         hipStream_t st) {
+    const int64_t n = rows * (inter / 8);
+    swiglu_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>((const uint8_t*)h, rows, inter, ldh * 2,
+                                                                     (uint8_t*)out, ldo * 2);
+    return launch_status();
+}
+
+}  // namespace ds3

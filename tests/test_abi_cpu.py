@@ -1,0 +1,83 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2412_19437_amd as p
+    if not os.path.exists(p.LIB_PATH):
+        from paper_2412_19437_amd.build import build_library
+        build_library(verbose=False)
+    return p
+
+
+def test_every_declared_symbol_is_exported(pkg):
+    header = open(os.path.join(ROOT, "include", "ds3.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ds3_[a-z0-9_]+)\s*\(", header))
+    assert {"ds3_quant_act_1x128", "ds3_quant_act_128x1", "ds3_quant_w_128x128",
+            "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs"} <= declared
+    lib = ctypes.CDLL(pkg.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(pkg.SYMBOLS)
+
+
+def test_status_strings(pkg):
+    seen = {pkg.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and pkg.status_string(0) == "ok" and pkg.status_string(99) == "unknown status"
+
+
+def test_quantizers_reject_bad_arguments_on_the_host(pkg):
+    L = pkg._L()
+    buf = (ctypes.c_uint8 * 4096)()
+    p = ctypes.addressof(buf)                      # host memory: never dereferenced, checks come first
+    p = (p + 15) & ~15
+    q = L.ds3_quant_act_1x128
+    assert q(None, 1, 4, 128, 128, p, 128, p, 1, 4, None) == 1          # NULL
+    assert q(p, 7, 4, 128, 128, p, 128, p, 1, 4, None) == 4             # dtype
+    assert q(p, 1, -1, 128, 128, p, 128, p, 1, 4, None) == 2            # negative rows
+    assert q(p, 1, 4, 128, 64, p, 128, p, 1, 4, None) == 2              # ld < cols
+    assert q(p, 1, 4, 132, 136, p, 144, p, 1, 4, None) == 3             # cols not a multiple of 8 (BF16)
+    assert q(p + 2, 1, 4, 128, 128, p, 128, p, 1, 4, None) == 3         # misaligned pointer
+    assert q(p, 1, 0, 128, 128, None, 128, None, 1, 4, None) == 0       # empty: no-op even with NULLs
+    w = L.ds3_quant_w_128x128
+    assert w(p, 0, 4, 130, 132, p, 144, p, None) == 3                   # FP32: cols % 4
+    assert w(p, 0, 4, 128, 128, None, 128, p, None) == 1
+    t = L.ds3_quant_act_128x1
+    assert t(p, 1, 130, 128, 128, p, 128, p, 1, 128, None) == 2         # ldq < rows
+    assert t(p, 1, 130, 128, 128, p, 136, p, 1, 128, None) == 3         # ldq % 16
+
+
+def test_gemm_rejects_bad_arguments_on_the_host(pkg):
+    L = pkg._L()
+    buf = (ctypes.c_uint8 * 4096)()
+    p = (ctypes.addressof(buf) + 15) & ~15
+    g = L.ds3_gemm_fp8_bs
+
+    def call(M=16, N=16, K=128, a=p, lda=128, sa=p, b=p, ldb=128, sb=p, mode=0, c=p, ct=1, ldc=16, acc=0):
+        return g(M, N, K, a, lda, sa, 1, M, b, ldb, sb, 1, 1, mode, c, ct, ldc, acc, None, 0, None)
+
+    assert call(K=100) == 2                       # K % 128
+    assert call(a=None) == 1
+    assert call(lda=64) == 2
+    assert call(lda=136) == 3
+    assert call(ldc=18) == 3
+    assert call(ct=1, acc=1) == 4                 # accumulate into BF16
+    assert call(mode=5) == 4
+    assert call(M=0, a=None, c=None) == 0         # empty
+    assert call(M=-1) == 2
+    gg = L.ds3_grouped_gemm_fp8_bs
+    assert gg(2, None, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 1
+    assert gg(0, None, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 0
+    assert L.ds3_gemm_fp8_bs_v(99, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, 1, 1, 0, p, 1, 16, 0, None, 0, None) == 5
+    assert L.ds3_swiglu(p, 4, 12, 24, p, 16, None) == 3
+    assert L.ds3_swiglu(None, 4, 16, 32, p, 16, None) == 1
+    assert pkg.ds3_gemm_workspace_bytes(4096, 18432, 7168) == 0
