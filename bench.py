@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the fine-grained FP8 linear layer on one MI355X.
+
+One "step" is one pass of the hot path over one batch of synthetic input at the
+DeepSeek-V3 dense-FFN up-projection shape (X[4096x7168] BF16, W[18432x7168]
+BF16): 1x128 quantization of X, 128x128 quantization of W and the block-scaled
+FP8 GEMM Y = X W^T in BF16.  Inputs are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5] [--no-cpu-baseline]
+
+The headline `value` is 2*M*N*K per step time (quantizers included) of the
+default workload; `kernels` lists every kernel of the step with its own
+roofline figure, measured with HIP events inside the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA, published
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-variant", type=int, default=-1)
+    return ap.parse_args()
+
+
+class Timed:
+    """A kernel launch bracketed by HIP events on the launching (current) stream."""
+
+    def __init__(self, name, fn, unit, work, bound, peak):
+        import torch
+        self.name, self.fn, self.unit, self.work, self.bound, self.peak = name, fn, unit, work, bound, peak
+        self.pairs = []
+        self._torch = torch
+
+    def __call__(self, record: bool):
+        if record:
+            e0 = self._torch.cuda.Event(enable_timing=True)
+            e1 = self._torch.cuda.Event(enable_timing=True)
+            e0.record()
+            self.fn()
+            e1.record()
+            self.pairs.append((e0, e1))
+        else:
+            self.fn()
+
+    def summary(self):
+        ms = sorted(a.elapsed_time(b) for a, b in self.pairs)
+        avg = sum(ms) / len(ms)
+        achieved = self.work / (avg * 1e-3)
+        return dict(name=self.name, avg_us=avg * 1e3, min_us=ms[0] * 1e3, bound=self.bound, achieved=achieved,
+                    peak=self.peak, unit=self.unit, frac=achieved / self.peak)
+
+
+def build_cfg2(ds3, torch, wl, dev, variant):
+    """Dense FFN up-projection Fprop.  Two input sets are rotated so that the
+    quantizers stream from HBM rather than from the 256 MB last-level cache."""
+    M, N, K = 4096, wl.DENSE_INTER, wl.HIDDEN
+    nsets = 2
+    x = wl.cfg2_x()
+    w = wl.cfg2_w()
+    xs = [torch.from_numpy(x).to(dev).to(torch.bfloat16) for _ in range(nsets)]
+    ws = [torch.from_numpy(w).to(dev).to(torch.bfloat16) for _ in range(nsets)]
+    del x, w
+    state = {"i": 0}
+    qa, sa = ds3.ds3_quant_act_1x128(xs[0])
+    qb, sb = ds3.ds3_quant_w_128x128(ws[0])
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    L = ds3._L()
+    st = torch.cuda.current_stream().cuda_stream
+
+    def quant_x():
+        xi = xs[state["i"] % nsets]
+        L.ds3_quant_act_1x128(xi.data_ptr(), ds3.DS3_BF16, M, K, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0),
+                              sa.stride(1), st)
+
+    def quant_w():
+        wi = ws[state["i"] % nsets]
+        L.ds3_quant_w_128x128(wi.data_ptr(), ds3.DS3_BF16, N, K, K, qb.data_ptr(), K, sb.data_ptr(), st)
+
+    def gemm():
+        r = L.ds3_gemm_fp8_bs_v(variant, M, N, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1),
+                                qb.data_ptr(), K, sb.data_ptr(), sb.stride(0), sb.stride(1), ds3.DS3_BSCALE_128x128,
+                                y.data_ptr(), ds3.DS3_BF16, N, 0, None, 0, st)
+        assert r == 0, r
+
+    bx = M * K * (2 + 1) + M * (K // 128) * 4
+    bw = N * K * (2 + 1) + (N // 128) * (K // 128) * 4
+    kernels = [
+        Timed("quant_act_1x128", quant_x, "GB/s", bx / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_w_128x128", quant_w, "GB/s", bw / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("gemm_fp8_bs", gemm, "TFLOP/s", 2.0 * M * N * K / 1e12, "mfma", PEAK_FP8_TFLOPS),
+    ]
+
+    def step(record):
+        for k in kernels:
+            k(record)
+        state["i"] += 1
+
+    cfg = {"workload": "cfg2: dense FFN up-projection Fprop, X[4096x7168] BF16 (1% outlier channels x50), "
+                       "W[18432x7168] BF16 ~N(0,0.02); quant 1x128 + quant 128x128 + block-scaled FP8 GEMM, BF16 out",
+           "M": M, "N": N, "K": K, "gemm_variant": variant}
+    return step, kernels, 2.0 * M * N * K, cfg, "gemm_fp8_bs"
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands on a bounded sample of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import ds3_oracle as orc
+    ms, ns, k = 512, 4608, wl.HIDDEN
+    x = wl.cfg2_x(m=ms)
+    w = wl.cfg2_w(n=ns)
+    t0 = time.perf_counter()
+    qa, sa = orc.quant_act_1x128(x)
+    qb, sb = orc.quant_w_128x128(w)
+    y = orc.gemm_fp8_bs(qa, sa, qb, sb)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(y).all()
+    threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+    return {"value": 2.0 * ms * ns * k / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "seconds": dt,
+            "sample": f"first {ms} rows of X and first {ns} rows of W of cfg2: oracle quant 1x128 + quant 128x128 + "
+                      f"FP64 GEMM {ms}x{ns}x{k}; numpy elementwise (1 thread) + OpenBLAS dgemm ({threads} threads)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures the single-GPU hot path only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2412_19437_amd as ds3
+    from synth import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    ds3._L()                                     # fail loudly if libds3.so has not been built
+    dev = "cuda:0"
+    if args.workload != "cfg2":
+        from paper_2412_19437_amd import bench_extra
+        step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant)
+    else:
+        step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ksum = [k.summary() for k in kernels]
+    dom = next(k for k in ksum if k["name"] == dominant)
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get(args.workload, {}).get(dominant)
+    out = {
+        "metric": "block-scaled FP8 GEMM TFLOP/s + % FP8 MFMA peak; quantizer GB/s + % HBM peak",
+        "value": flops * args.steps / dt / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
+        "config": cfg,
+        "roofline": {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
+                     "frac": dom["frac"], "traffic": traffic, "kernel": dom["name"], "avg_us": dom["avg_us"]},
+        "kernels": ksum,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

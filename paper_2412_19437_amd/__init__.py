@@ -100,6 +100,18 @@ def _rows2d(t: torch.Tensor, name: str):
     return t.shape[0], t.shape[1], t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
 
 
+def _codes(rows: int, cols: int, device) -> torch.Tensor:
+    """uint8 [rows][cols] whose leading dimension is padded to a multiple of 16."""
+    ld = (cols + 15) // 16 * 16
+    return torch.empty((rows, ld), dtype=torch.uint8, device=device)[:, :cols]
+
+
+def _out(rows: int, cols: int, dtype, device) -> torch.Tensor:
+    """GEMM output [rows][cols] whose leading dimension is padded to a multiple of 8 elements."""
+    ld = (cols + 7) // 8 * 8
+    return torch.empty((rows, ld), dtype=dtype, device=device)[:, :cols]
+
+
 def _scales(rows: int, blocks: int, device, k_major: bool) -> torch.Tensor:
     """Logical [rows][blocks] FP32 tensor; k_major stores it as [blocks][rows]."""
     if k_major:
@@ -110,9 +122,9 @@ def _scales(rows: int, blocks: int, device, k_major: bool) -> torch.Tensor:
 def ds3_quant_act_1x128(x: torch.Tensor, k_major_scales: bool = True):
     """x [M][K] FP32/BF16 -> (codes uint8 [M][K], scales FP32 logical [M][ceil(K/128)])."""
     m, k, ldx = _rows2d(x, "x")
-    q = torch.empty((m, k), dtype=torch.uint8, device=x.device)
+    q = _codes(m, k, x.device)
     s = _scales(m, (k + 127) // 128, x.device, k_major_scales)
-    st = _L().ds3_quant_act_1x128(x.data_ptr(), _dt(x), m, k, ldx, q.data_ptr(), k,
+    st = _L().ds3_quant_act_1x128(x.data_ptr(), _dt(x), m, k, ldx, q.data_ptr(), (k + 15) // 16 * 16,
                                  s.data_ptr(), s.stride(0), s.stride(1), _stream())
     _check(st, "ds3_quant_act_1x128")
     return q, s
@@ -122,7 +134,7 @@ def ds3_quant_act_128x1(x: torch.Tensor, k_major_scales: bool = True):
     """x [T][C] -> (codes uint8 [C][T] token-contiguous, scales logical [C][ceil(T/128)])."""
     t, c, ldx = _rows2d(x, "x")
     ldq = (t + 15) // 16 * 16
-    q_t = torch.empty((c, ldq), dtype=torch.uint8, device=x.device)[:, :t]
+    q_t = _codes(c, t, x.device)
     s_t = _scales(c, (t + 127) // 128, x.device, k_major_scales)
     st = _L().ds3_quant_act_128x1(x.data_ptr(), _dt(x), t, c, ldx, q_t.data_ptr(), ldq,
                                  s_t.data_ptr(), s_t.stride(0), s_t.stride(1), _stream())
@@ -133,9 +145,10 @@ def ds3_quant_act_128x1(x: torch.Tensor, k_major_scales: bool = True):
 def ds3_quant_w_128x128(w: torch.Tensor):
     """w [N][K] -> (codes uint8 [N][K], scales FP32 [ceil(N/128)][ceil(K/128)])."""
     n, k, ldw = _rows2d(w, "w")
-    q = torch.empty((n, k), dtype=torch.uint8, device=w.device)
+    q = _codes(n, k, w.device)
     s = torch.empty(((n + 127) // 128, (k + 127) // 128), dtype=torch.float32, device=w.device)
-    st = _L().ds3_quant_w_128x128(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), k, s.data_ptr(), _stream())
+    st = _L().ds3_quant_w_128x128(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), (k + 15) // 16 * 16, s.data_ptr(),
+                                  _stream())
     _check(st, "ds3_quant_w_128x128")
     return q, s
 
@@ -150,7 +163,7 @@ def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=t
     if kb_ != k:
         raise ValueError("a and b disagree on K")
     if c is None:
-        c = torch.empty((m, n), dtype=out_dtype, device=a.device)
+        c = _out(m, n, out_dtype, a.device)
     _, _, ldc = _rows2d(c, "c")
     st = _L().ds3_gemm_fp8_bs_v(variant, m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1),
                                b.data_ptr(), ldb, sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode,
@@ -170,7 +183,7 @@ def ds3_grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat1
     if group_offsets.dtype != torch.int32 or group_offsets.numel() != g + 1:
         raise ValueError("group_offsets must be int32 of length G+1")
     if c is None:
-        c = torch.empty((m, n), dtype=out_dtype, device=a.device)
+        c = _out(m, n, out_dtype, a.device)
     _, _, ldc = _rows2d(c, "c")
     st = _L().ds3_grouped_gemm_fp8_bs_v(variant, g, group_offsets.data_ptr(), m, n, k, a.data_ptr(), lda,
                                        sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), k, sb.data_ptr(),

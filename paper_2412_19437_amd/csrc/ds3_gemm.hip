@@ -14,7 +14,7 @@
 // Data path: 128-byte K-rows of both operands go global -> LDS with 128-bit
 // accesses (optionally straight into LDS, bypassing registers), two stages;
 // LDS rows are 128 bytes with the eight 16-byte chunks XOR-swizzled by
-// (row ^ row>>3) & 7 so that the 16 rows x 2 chunks a fragment read touches
+// (row & 7) ^ (row>>3 & 1) so that the 16 rows x 2 chunks a fragment read touches
 // fall into distinct banks.  Workgroup ids are remapped so that each XCD (one
 // L2 each, workgroups are dealt round-robin to the 8 XCDs) walks a compact
 // panel of output tiles.
@@ -45,7 +45,8 @@ struct Cfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
-__device__ __forceinline__ int swz_key(int row) { return (row ^ (row >> 3)) & 7; }
+// XOR key of a tile row: depends on the row's position inside its 16-row fragment only.
+__device__ __forceinline__ int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
@@ -337,7 +338,7 @@ int gemm_num_variants() { return 6; }
 ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
     if (variant < 0) {
         // default choice by shape: grouped problems and small-M problems take the narrower M tile
-        variant = (p.G > 0) ? 2 : 0;
+        variant = (p.G > 0) ? 3 : 1;
     }
     switch (variant) {
         case 0: return launch_cfg<Cfg<256, 256, 4, 2, false>>(p, ct, mode, st);
