@@ -11,13 +11,21 @@
 // row and four consecutive weight rows, so the scale product
 // sa(m,kb) * sb(n/128,kb) is a single per-lane value per activation fragment.
 //
-// Data path: 128-byte K-rows of both operands go global -> LDS with 128-bit
-// accesses (optionally straight into LDS, bypassing registers), two stages;
-// LDS rows are 128 bytes with the eight 16-byte chunks XOR-swizzled by
-// (row & 7) ^ (row>>3 & 1) so that the 16 rows x 2 chunks a fragment read touches
-// fall into distinct banks.  Workgroup ids are remapped so that each XCD (one
-// L2 each, workgroups are dealt round-robin to the 8 XCDs) walks a compact
-// panel of output tiles.
+// Data path: 128-byte K-rows of both operands go global -> LDS directly
+// (buffer loads with the LDS bit, 16 bytes per lane, no staging registers),
+// two LDS stages.  LDS rows are 128 bytes with the eight 16-byte chunks
+// XOR-swizzled by (row & 7) ^ (row>>3 & 1) so that the 16 rows x 2 chunks of a
+// fragment read fall into distinct banks.  Workgroup ids are remapped so that
+// each XCD (one L2 each; workgroups are dealt round-robin to the 8 XCDs) walks
+// a compact panel of output tiles.
+//
+// Pipeline of one K-step (per wave): all sub-tiles but those of the last
+// activation fragment are computed from registers / the current stage; then
+// ONE workgroup barrier (next stage complete, current stage free); then, in
+// the shadow of the last fragment's MFMAs, the loads for K-step kb+2 are
+// issued into the freed stage and the first fragments and scales of K-step
+// kb+1 are read from LDS, so the matrix pipe never waits for LDS at the start
+// of a K-step.
 #include <type_traits>
 
 #include "ds3_dev.h"
@@ -27,30 +35,36 @@ namespace ds3 {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-template <int BN_, int BM_, int WN_, int WM_, bool DIRECT_>
+template <int BN_, int BM_, int WN_, int WM_>
 struct Cfg {
     static constexpr int BN = BN_, BM = BM_, WN = WN_, WM = WM_;
-    static constexpr bool DIRECT = DIRECT_;
     static constexpr int NT = 64 * WN * WM;
     static constexpr int TN = BN / WN, TM = BM / WM;   // wave tile
     static constexpr int FN = TN / 16, FM = TM / 16;   // 16-row fragments per wave
+    static constexpr int NSUB = FN * FM;               // 16x16 sub-tiles (= MFMAs per K-step) per wave
     static constexpr int ROWS = BN + BM;
     static constexpr int STAGE = ROWS * 128;           // bytes of codes per K-step
     static constexpr int RPI = NT / 8;                 // tile rows one load instruction of the workgroup covers
     static constexpr int LPT = ROWS / RPI;             // 16-byte loads per thread per K-step
-    static constexpr int LDS_BYTES = 2 * STAGE + 4 * NT * 4;     // codes + [2][NT] sa + [2][NT] per-row sb
+    static constexpr int LDS_BYTES = 2 * STAGE + 4 * NT * 4;   // codes + [2][NT] sa + [2][NT] per-row sb
     static_assert(ROWS % RPI == 0 && BN % RPI == 0 && RPI % 16 == 0, "load mapping");
     static_assert(BM <= NT && BN <= NT, "scale staging uses one thread per row");
     static_assert(TN <= 128 && 128 % TN == 0, "one weight-scale block per wave");
+    static_assert(FM % 2 == 0 && FM >= 2, "activation fragments are double-buffered");
+    static_assert(LPT <= 2 * FN, "loads are interleaved with the last fragment's MFMAs");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
 // XOR key of a tile row: depends on the row's position inside its 16-row fragment only.
 __device__ __forceinline__ int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
+// Offset that is out of range for every descriptor this kernel builds (their
+// sizes are below 2^31): a load with it moves no data.
+constexpr unsigned kOobOffset = 0x80000000u;
+
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
-    constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE;
+    constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE, NSUB = C::NSUB;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[C::LDS_BYTES];
     float* const sa_s = reinterpret_cast<float*>(smem + 2 * STAGE);            // [2][NT], first BM used
     float* const sbrow_s = sa_s + 2 * NT;                                      // [2][NT], first BN used (per-row mode)
@@ -96,8 +110,10 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 
     const uint8_t* a_tile = p.a + (int64_t)m0 * p.lda;
     const uint8_t* b_tile = p.b + (int64_t)grp * p.b_group_stride + (int64_t)n0 * p.ldb;
-    // Buffer descriptors bound to the valid bytes of the tile: rows past the
-    // end of the matrix (or of the expert's group) read as zero.
+    // Buffer descriptors bound to the valid bytes of the tile.  The whole byte
+    // offset of a load goes into the per-lane offset operand, which the
+    // hardware range-checks: rows past the end of the matrix (or of the
+    // expert's group) read as zero and touch no memory.
     const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
         (void*)a_tile, 0, (int)((int64_t)(m_rows - 1) * p.lda + p.K), 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
@@ -106,9 +122,9 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     // load mapping: this thread moves chunk position (tid & 7) of tile row i*RPI + (tid >> 3)
     const int lrow = tid >> 3;
     const int gchunk = (tid & 7) ^ swz_key(lrow);      // which 16 bytes of the K-row land there
-    const int voff_b = lrow * (int)p.ldb + gchunk * 16;
-    const int voff_a = lrow * (int)p.lda + gchunk * 16;
-    const int step_b = C::RPI * (int)p.ldb, step_a = C::RPI * (int)p.lda;
+    const unsigned voff_b = (unsigned)(lrow * (int)p.ldb + gchunk * 16);
+    const unsigned voff_a = (unsigned)(lrow * (int)p.lda + gchunk * 16);
+    const unsigned step_b = (unsigned)(C::RPI * (int)p.ldb), step_a = (unsigned)(C::RPI * (int)p.lda);
 
     // fragment read offsets inside a 16-row group: lane reads chunks 2*g4 and 2*g4+1 of row l16
     const int key = swz_key(l16);
@@ -127,41 +143,40 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         const int nb = min((n0 + wn * C::TN) >> 7, nblocks - 1);
         sb_blk = p.sb + (int64_t)grp * p.sb_group_stride + (int64_t)nb * p.sbr;
     }
-
-    u32x4 stg[C::DIRECT ? 1 : C::LPT];
-    float sa_reg = 0.f, sbrow_reg = 0.f;
     // Every thread stages one activation scale (and one per-row weight scale);
     // threads past the valid rows re-read the last valid row, whose partial
     // sums are zero because its codes were read as zero.
     const float* sa_thr = sa_tile + (int64_t)min(tid, m_rows - 1) * p.sar;
     const float* sbrow_thr = ROWSB ? sb_blk + (int64_t)min(tid, n_rows - 1) * p.sbr : nullptr;
+    float sa_reg = 0.f, sbrow_reg = 0.f;
 
-    auto issue_loads = [&](int kb, int stage) {
-        const int koff = kb << 7;
-#pragma unroll
-        for (int i = 0; i < C::LPT; ++i) {
-            const bool is_b = i * C::RPI < BN;
-            const int ii = is_b ? i : i - BN / C::RPI;
-            const int voff = is_b ? voff_b : voff_a;
-            const int soff = koff + ii * (is_b ? step_b : step_a);
-            if constexpr (C::DIRECT) {
-                uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? rs_b : rs_a, (lds_ptr_t)dst, 16, voff, soff, 0, 0);
-            } else {
-                stg[i] = __builtin_amdgcn_raw_buffer_load_b128(is_b ? rs_b : rs_a, voff, soff, 0);
-            }
-        }
+    // i-th 16-byte load of this thread for the K-step at byte offset koff, into LDS stage `stage`
+    auto issue_load = [&](int i, int stage, unsigned koff) {
+        const bool is_b = i * C::RPI < BN;
+        const int ii = is_b ? i : i - BN / C::RPI;
+        const unsigned voff = (is_b ? voff_b : voff_a) + (koff + (unsigned)ii * (is_b ? step_b : step_a));
+        uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? rs_b : rs_a, (lds_ptr_t)dst, 16, (int)voff, 0, 0, 0);
+    };
+    auto load_scales = [&](int kb) {                   // global -> registers
         sa_reg = sa_thr[(int64_t)kb * p.sak];
         if constexpr (ROWSB) sbrow_reg = sbrow_thr[(int64_t)kb * p.sbk];
     };
-    auto commit_loads = [&](int stage) {
-        if constexpr (!C::DIRECT) {
-#pragma unroll
-            for (int i = 0; i < C::LPT; ++i)
-                *reinterpret_cast<u32x4*>(smem + stage * STAGE + (i * NT + tid) * 16) = stg[i];
-        }
+    auto commit_scales = [&](int stage) {              // registers -> LDS
         sa_s[stage * NT + tid] = sa_reg;
         if constexpr (ROWSB) sbrow_s[stage * NT + tid] = sbrow_reg;
+    };
+    auto load_frag = [&](const uint8_t* base) -> i32x8 {
+        const i32x4 lo = *reinterpret_cast<const i32x4*>(base + foff0);
+        const i32x4 hi = *reinterpret_cast<const i32x4*>(base + foff1);
+        return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+    auto read_tj = [&](int stage, float sbv, float* tj) {
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const float sav = sa_s[stage * NT + wm * C::TM + j * 16 + l16];
+            tj[j] = ROWSB ? sav : sav * sbv;
+        }
     };
 
     f32x4 acc[FN][FM];
@@ -170,54 +185,78 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 #pragma unroll
         for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto load_frag = [&](const uint8_t* base) -> i32x8 {
-        const i32x4 lo = *reinterpret_cast<const i32x4*>(base + foff0);
-        const i32x4 hi = *reinterpret_cast<const i32x4*>(base + foff1);
-        return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    };
-
-    // One K-step of this wave on LDS stage `stage`.  The instruction order is
-    // pinned by hand: the MFMA of sub-tile s is issued, then the four FMAs that
-    // fold sub-tile s-D into the accumulators, so the vector ALU works in the
-    // shadow of the matrix pipe.  The empty asm statements only tie values to
-    // program points (they emit nothing): without them the compiler gathers all
-    // MFMAs first and all FMAs last.
-    constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
-    auto compute = [&](int stage, float sbv) {
-        const uint8_t* st = smem + stage * STAGE;
-        float tj[FM];
+    // ---- prologue: K-step 0 into stage 0, K-step 1 in flight into stage 1 -----------
 #pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const float sav = sa_s[stage * NT + wm * C::TM + j * 16 + l16];
-            tj[j] = ROWSB ? sav : sav * sbv;
-        }
+    for (int i = 0; i < C::LPT; ++i) issue_load(i, 0, 0u);
+    load_scales(0);
+    commit_scales(0);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < C::LPT; ++i) issue_load(i, 1, KB > 1 ? 128u : kOobOffset);
+    load_scales(min(1, KB - 1));
+    float sb_n = ROWSB ? 1.f : sb_blk[(int64_t)min(1, KB - 1) * p.sbk];      // block scale of the NEXT K-step
+    float tj[FM];
+    read_tj(0, ROWSB ? 1.f : sb_blk[0], tj);
+    i32x8 pf[FN], qf[2];
+#pragma unroll
+    for (int i = 0; i < FN; ++i) pf[i] = load_frag(smem + p_base + i * 2048);
+    qf[0] = load_frag(smem + q_base);
+
+    // One K-step from LDS stage S.  The instruction order is pinned by hand:
+    // the MFMA of sub-tile s is issued, then the four FMAs that fold sub-tile
+    // s-D into the accumulators, so the vector ALU works in the shadow of the
+    // matrix pipe.  The empty asm statements only tie values to program points
+    // (they emit nothing); without them the compiler gathers all MFMAs first
+    // and all FMAs last.
+    constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
+    auto kstep = [&](int kb, auto stage_tag) {
+        constexpr int S = decltype(stage_tag)::value;
+        const uint8_t* st = smem + S * STAGE;
+        const uint8_t* nst = smem + (S ^ 1) * STAGE;
         f32x4 un[FN];
         if constexpr (ROWSB) {
 #pragma unroll
             for (int i = 0; i < FN; ++i)
-                un[i] = *reinterpret_cast<const f32x4*>(sbrow_s + stage * NT + wn * C::TN + i * 16 + g4 * 4);
+                un[i] = *reinterpret_cast<const f32x4*>(sbrow_s + S * NT + wn * C::TN + i * 16 + g4 * 4);
         }
-        i32x8 pf[FN];
-#pragma unroll
-        for (int i = 0; i < FN; ++i) pf[i] = load_frag(st + p_base + i * 2048);
-        i32x8 qf[2];
-        qf[0] = load_frag(st + q_base);
         f32x4 part[D + 1];
 #pragma unroll
         for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float tjn[FM];                                  // scale products of the next K-step
+        const unsigned koff2 = kb + 2 < KB ? (unsigned)(kb + 2) << 7 : kOobOffset;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < FN * FM + D; ++s) {
-            if (s < FN * FM) {
+        for (int s = 0; s < NSUB + D; ++s) {
+            if (s == NSUB - FN) {
+                // Everything this wave reads from stage S is in registers.  After the
+                // barrier stage S^1 is complete and stage S may be overwritten.
+                commit_scales(S ^ 1);
+                __syncthreads();
+                load_scales(min(kb + 2, KB - 1));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (s < NSUB) {
                 const int j = s / FN, i = s % FN;
                 if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
                 part[s % (D + 1)] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                     pf[i], qf[j & 1], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+                if (j == FM - 1) {
+                    // last activation fragment: refill this weight fragment for the next
+                    // K-step and push the loads of K-step kb+2 into the freed stage
+                    pf[i] = load_frag(nst + p_base + i * 2048);
+                    if (2 * i < C::LPT) issue_load(2 * i, S, koff2);
+                    if (2 * i + 1 < C::LPT) issue_load(2 * i + 1, S, koff2);
+                    if (i == FN - 1) {
+                        qf[0] = load_frag(nst + q_base);
+                        read_tj(S ^ 1, sb_n, tjn);
+                        if constexpr (!ROWSB) sb_n = sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
+                    }
+                }
             }
             if (s >= D) {
                 const int ps = s - D, j = ps / FN, i = ps % FN;
                 // the MFMA just issued comes before the FMAs of sub-tile ps
-                if (s < FN * FM) asm volatile("" : "+v"(part[s % (D + 1)]), "+v"(part[ps % (D + 1)]));
+                if (s < NSUB) asm volatile("" : "+v"(part[s % (D + 1)]), "+v"(part[ps % (D + 1)]));
                 const f32x4 pr = part[ps % (D + 1)];
                 f32x4 a = acc[i][j];
                 if constexpr (ROWSB) {
@@ -236,39 +275,18 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
     };
 
-    // ---- main loop: two LDS stages, loads for K-step kb+1 fly during compute of kb ----
-    // step(kb, S, more): compute K-step kb from stage S; when `more`, fetch K-step kb+1 into stage S^1.
-    float sb_next = ROWSB ? 1.f : sb_blk[0];
-    auto step = [&](int kb, int stage, auto more_tag) {
-        constexpr bool more = decltype(more_tag)::value;
-        const float sbv = sb_next;
-        if constexpr (more) {
-            issue_loads(kb + 1, stage ^ 1);
-            if constexpr (!ROWSB) sb_next = sb_blk[(int64_t)(kb + 1) * p.sbk];
-        }
-        compute(stage, sbv);
-        if constexpr (more) commit_loads(stage ^ 1);
-        __syncthreads();
-    };
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
-    issue_loads(0, 0);
-    commit_loads(0);
-    __syncthreads();
+    using st0 = std::integral_constant<int, 0>;
+    using st1 = std::integral_constant<int, 1>;
     int kb = 0;
-    for (; kb + 2 < KB; kb += 2) {
-        step(kb, 0, yes{});
-        step(kb + 1, 1, yes{});
+    for (; kb + 1 < KB; kb += 2) {
+        kstep(kb, st0{});
+        kstep(kb + 1, st1{});
     }
-    // one or two K-steps remain
-    if (kb + 2 == KB) {
-        step(kb, 0, yes{});
-        step(kb + 1, 1, no{});
-    } else {
-        step(kb, 0, no{});
-    }
+    if (kb < KB) kstep(kb, st0{});
 
     // ---- epilogue: lane owns activation row m and, per weight fragment, 4 consecutive n ----
     constexpr int ESZ = OUT_BF16 ? 2 : 4;
@@ -316,8 +334,8 @@ static ds3_status launch_one(GemmParams p, hipStream_t st) {
     const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
     if (ntiles <= 0) return DS3_OK;
     if (ntiles > (1 << 28)) return DS3_ERR_UNSUPPORTED;
-    // 32-bit byte offsets inside one tile's rows
-    if ((int64_t)C::BN * p.ldb + p.K >= (1ll << 31) || (int64_t)C::BM * p.lda + p.K >= (1ll << 31))
+    // 32-bit byte offsets inside one tile's rows, all below the out-of-range marker
+    if ((int64_t)(C::BN + 1) * p.ldb + p.K >= (1ll << 31) || (int64_t)(C::BM + 1) * p.lda + p.K >= (1ll << 31))
         return DS3_ERR_UNSUPPORTED;
     const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
     gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
@@ -333,20 +351,17 @@ static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode,
     return bf16 ? launch_one<C, false, true, false>(p, st) : launch_one<C, false, false, false>(p, st);
 }
 
-int gemm_num_variants() { return 6; }
+int gemm_num_variants() { return 3; }
 
 ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
     if (variant < 0) {
-        // default choice by shape: grouped problems and small-M problems take the narrower M tile
-        variant = (p.G > 0) ? 3 : 1;
+        // default choice by shape: grouped problems take the narrower M tile
+        variant = (p.G > 0) ? 1 : 0;
     }
     switch (variant) {
-        case 0: return launch_cfg<Cfg<256, 256, 4, 2, false>>(p, ct, mode, st);
-        case 1: return launch_cfg<Cfg<256, 256, 4, 2, true>>(p, ct, mode, st);
-        case 2: return launch_cfg<Cfg<256, 128, 4, 2, false>>(p, ct, mode, st);
-        case 3: return launch_cfg<Cfg<256, 128, 4, 2, true>>(p, ct, mode, st);
-        case 4: return launch_cfg<Cfg<128, 128, 2, 2, false>>(p, ct, mode, st);
-        case 5: return launch_cfg<Cfg<128, 128, 2, 2, true>>(p, ct, mode, st);
+        case 0: return launch_cfg<Cfg<256, 256, 4, 2>>(p, ct, mode, st);
+        case 1: return launch_cfg<Cfg<256, 128, 4, 2>>(p, ct, mode, st);
+        case 2: return launch_cfg<Cfg<128, 128, 2, 2>>(p, ct, mode, st);
         default: return DS3_ERR_UNSUPPORTED;
     }
 }
