@@ -62,6 +62,16 @@ __device__ __forceinline__ int swz_key(int row) { return (row & 7) ^ ((row >> 3)
 // sizes are below 2^31): a load with it moves no data.
 constexpr unsigned kOobOffset = 0x80000000u;
 
+// What a workgroup needs to know about one output tile (all wave-uniform
+// except the two per-thread scale pointers).
+struct TileCtx {
+    int m0, n0, m_rows, n_rows;
+    __amdgpu_buffer_rsrc_t rs_a, rs_b;
+    const float* sb_blk;      // block mode: this wave's block row of scales; row mode: tile base
+    const float* sa_thr;      // this thread's activation-scale row
+    const float* sbrow_thr;   // this thread's weight-scale row (per-row mode)
+};
+
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
     constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE, NSUB = C::NSUB;
@@ -74,50 +84,68 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % C::WN, wm = wave / C::WN;
     const int l16 = lane & 15, g4 = lane >> 4;
-
-    // ---- which output tile ------------------------------------------------------
-    const int ntiles = p.tiles_m * p.tiles_n;
-    const int per_xcd = (ntiles + 7) >> 3;
-    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (t >= ntiles) return;
-    int m0, m_end, n0, grp = 0;
-    if constexpr (!GROUPED) {
-        constexpr int PM = 4;                          // tiles of M per panel
-        const int panel = PM * p.tiles_n;
-        const int pi = t / panel, r = t - pi * panel;
-        const int pm = min(PM, p.tiles_m - pi * PM);
-        m0 = (pi * PM + r % pm) * BM;
-        n0 = (r / pm) * BN;
-        m_end = p.M;
-    } else {
-        const int mt = t / p.tiles_n;
-        n0 = (t - mt * p.tiles_n) * BN;
-        int cum = 0, lo = p.group_offsets[0];
-        m0 = -1; m_end = 0;
-        for (int g = 0; g < p.G; ++g) {
-            const int hi = p.group_offsets[g + 1];
-            const int nt_g = (hi - lo + BM - 1) / BM;
-            if (m0 < 0 && mt < cum + nt_g) { grp = g; m0 = lo + (mt - cum) * BM; m_end = hi; }
-            cum += nt_g;
-            lo = hi;
-        }
-        if (m0 < 0) return;
-        m_end = min(m_end, p.M);
-    }
-    const int m_rows = min(m_end - m0, BM);            // valid rows of this tile (>= 1)
-    const int n_rows = min(p.N - n0, BN);
     const int KB = p.K >> 7;
 
-    const uint8_t* a_tile = p.a + (int64_t)m0 * p.lda;
-    const uint8_t* b_tile = p.b + (int64_t)grp * p.b_group_stride + (int64_t)n0 * p.ldb;
-    // Buffer descriptors bound to the valid bytes of the tile.  The whole byte
-    // offset of a load goes into the per-lane offset operand, which the
-    // hardware range-checks: rows past the end of the matrix (or of the
-    // expert's group) read as zero and touch no memory.
-    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)a_tile, 0, (int)((int64_t)(m_rows - 1) * p.lda + p.K), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)b_tile, 0, (int)((int64_t)(n_rows - 1) * p.ldb + p.K), 0x00020000);
+    // ---- persistent tile walk ------------------------------------------------------
+    // Workgroup b runs on XCD b % 8.  The tile list is cut into 8 contiguous
+    // chunks, one per XCD; the workgroups of an XCD take consecutive tiles of
+    // their chunk, so the tiles in flight on one L2 form a compact panel.
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int per_xcd = (ntiles + 7) >> 3;
+    const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslots = (int)(gridDim.x >> 3);
+
+    auto setup_tile = [&](int local, TileCtx& c) -> bool {
+        const int t = xcd * per_xcd + local;
+        if (local >= per_xcd || t >= ntiles) return false;
+        int m0, m_end, n0, grp = 0;
+        if constexpr (!GROUPED) {
+            constexpr int PM = 4;                      // tiles of M per panel
+            const int panel = PM * p.tiles_n;
+            const int pi = t / panel, r = t - pi * panel;
+            const int pm = min(PM, p.tiles_m - pi * PM);
+            m0 = (pi * PM + r % pm) * BM;
+            n0 = (r / pm) * BN;
+            m_end = p.M;
+        } else {
+            const int mt = t / p.tiles_n;
+            n0 = (t - mt * p.tiles_n) * BN;
+            int cum = 0, lo = p.group_offsets[0];
+            m0 = -1; m_end = 0;
+            for (int g = 0; g < p.G; ++g) {
+                const int hi = p.group_offsets[g + 1];
+                const int nt_g = (hi - lo + BM - 1) / BM;
+                if (m0 < 0 && mt < cum + nt_g) { grp = g; m0 = lo + (mt - cum) * BM; m_end = hi; }
+                cum += nt_g;
+                lo = hi;
+            }
+            if (m0 < 0) return false;                  // past the last expert: tiles are ordered, nothing follows
+            m_end = min(m_end, p.M);
+        }
+        c.m0 = m0; c.n0 = n0;
+        c.m_rows = min(m_end - m0, BM);                // valid rows of this tile (>= 1)
+        c.n_rows = min(p.N - n0, BN);
+        const uint8_t* a_tile = p.a + (int64_t)m0 * p.lda;
+        const uint8_t* b_tile = p.b + (int64_t)grp * p.b_group_stride + (int64_t)n0 * p.ldb;
+        // Buffer descriptors bound to the valid bytes of the tile.  The whole byte
+        // offset of a load goes into the per-lane offset operand, which the
+        // hardware range-checks: rows past the end of the matrix (or of the
+        // expert's group) read as zero and touch no memory.
+        c.rs_a = __builtin_amdgcn_make_buffer_rsrc((void*)a_tile, 0, (int)((int64_t)(c.m_rows - 1) * p.lda + p.K), 0x00020000);
+        c.rs_b = __builtin_amdgcn_make_buffer_rsrc((void*)b_tile, 0, (int)((int64_t)(c.n_rows - 1) * p.ldb + p.K), 0x00020000);
+        if constexpr (ROWSB) {
+            c.sb_blk = p.sb + (int64_t)n0 * p.sbr;
+        } else {
+            const int nblocks = (p.N + 127) >> 7;
+            const int nb = min((n0 + wn * C::TN) >> 7, nblocks - 1);
+            c.sb_blk = p.sb + (int64_t)grp * p.sb_group_stride + (int64_t)nb * p.sbr;
+        }
+        // Every thread stages one activation scale (and one per-row weight scale);
+        // threads past the valid rows re-read the last valid row, whose partial
+        // sums are zero because its codes were read as zero.
+        c.sa_thr = p.sa + ((int64_t)m0 + min(tid, c.m_rows - 1)) * p.sar;
+        c.sbrow_thr = ROWSB ? c.sb_blk + (int64_t)min(tid, c.n_rows - 1) * p.sbr : nullptr;
+        return true;
+    };
 
     // load mapping: this thread moves chunk position (tid & 7) of tile row i*RPI + (tid >> 3)
     const int lrow = tid >> 3;
@@ -133,34 +161,19 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int p_base = wn * C::TN * 128;               // weight fragments of this wave
     const int q_base = (BN + wm * C::TM) * 128;        // activation fragments of this wave
 
-    // scales
-    const float* sa_tile = p.sa + (int64_t)m0 * p.sar;
-    const float* sb_blk;                               // block mode: this wave's block row; row mode: tile base
-    if constexpr (ROWSB) {
-        sb_blk = p.sb + (int64_t)n0 * p.sbr;
-    } else {
-        const int nblocks = (p.N + 127) >> 7;
-        const int nb = min((n0 + wn * C::TN) >> 7, nblocks - 1);
-        sb_blk = p.sb + (int64_t)grp * p.sb_group_stride + (int64_t)nb * p.sbr;
-    }
-    // Every thread stages one activation scale (and one per-row weight scale);
-    // threads past the valid rows re-read the last valid row, whose partial
-    // sums are zero because its codes were read as zero.
-    const float* sa_thr = sa_tile + (int64_t)min(tid, m_rows - 1) * p.sar;
-    const float* sbrow_thr = ROWSB ? sb_blk + (int64_t)min(tid, n_rows - 1) * p.sbr : nullptr;
     float sa_reg = 0.f, sbrow_reg = 0.f;
 
     // i-th 16-byte load of this thread for the K-step at byte offset koff, into LDS stage `stage`
-    auto issue_load = [&](int i, int stage, unsigned koff) {
+    auto issue_load = [&](const TileCtx& c, int i, int stage, unsigned koff) {
         const bool is_b = i * C::RPI < BN;
         const int ii = is_b ? i : i - BN / C::RPI;
         const unsigned voff = (is_b ? voff_b : voff_a) + (koff + (unsigned)ii * (is_b ? step_b : step_a));
         uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? rs_b : rs_a, (lds_ptr_t)dst, 16, (int)voff, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? c.rs_b : c.rs_a, (lds_ptr_t)dst, 16, (int)voff, 0, 0, 0);
     };
-    auto load_scales = [&](int kb) {                   // global -> registers
-        sa_reg = sa_thr[(int64_t)kb * p.sak];
-        if constexpr (ROWSB) sbrow_reg = sbrow_thr[(int64_t)kb * p.sbk];
+    auto load_scales = [&](const TileCtx& c, int kb) { // global -> registers
+        sa_reg = c.sa_thr[(int64_t)kb * p.sak];
+        if constexpr (ROWSB) sbrow_reg = c.sbrow_thr[(int64_t)kb * p.sbk];
     };
     auto commit_scales = [&](int stage) {              // registers -> LDS
         sa_s[stage * NT + tid] = sa_reg;
@@ -179,153 +192,208 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         }
     };
 
-    f32x4 acc[FN][FM];
+    TileCtx cur;
+    int local = slot;
+    if (!setup_tile(local, cur)) return;
+    // K-step 0 of the first tile into stage 0
 #pragma unroll
-    for (int i = 0; i < FN; ++i)
-#pragma unroll
-        for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < C::LPT; ++i) issue_load(cur, i, 0, 0u);
+    load_scales(cur, 0);
 
-    // ---- prologue: K-step 0 into stage 0, K-step 1 in flight into stage 1 -----------
+    for (;;) {
+        // ---- entry: K-step 0 of `cur` is in flight into stage 0, its scales are in registers ----
+        commit_scales(0);
+        __syncthreads();
+        float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
+        float tj[FM];
+        read_tj(0, ROWSB ? 1.f : cur.sb_blk[0], tj);
+        i32x8 pf[FN], qf[2];
 #pragma unroll
-    for (int i = 0; i < C::LPT; ++i) issue_load(i, 0, 0u);
-    load_scales(0);
-    commit_scales(0);
-    __syncthreads();
+        for (int i = 0; i < FN; ++i) pf[i] = load_frag(smem + p_base + i * 2048);
+        qf[0] = load_frag(smem + q_base);
+        f32x4 acc[FN][FM];
 #pragma unroll
-    for (int i = 0; i < C::LPT; ++i) issue_load(i, 1, KB > 1 ? 128u : kOobOffset);
-    load_scales(min(1, KB - 1));
-    float sb_n = ROWSB ? 1.f : sb_blk[(int64_t)min(1, KB - 1) * p.sbk];      // block scale of the NEXT K-step
-    float tj[FM];
-    read_tj(0, ROWSB ? 1.f : sb_blk[0], tj);
-    i32x8 pf[FN], qf[2];
+        for (int i = 0; i < FN; ++i)
 #pragma unroll
-    for (int i = 0; i < FN; ++i) pf[i] = load_frag(smem + p_base + i * 2048);
-    qf[0] = load_frag(smem + q_base);
+            for (int j = 0; j < FM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // One K-step from LDS stage S.  The instruction order is pinned by hand:
-    // the MFMA of sub-tile s is issued, then the four FMAs that fold sub-tile
-    // s-D into the accumulators, so the vector ALU works in the shadow of the
-    // matrix pipe.  The empty asm statements only tie values to program points
-    // (they emit nothing); without them the compiler gathers all MFMAs first
-    // and all FMAs last.
-    constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
-    auto kstep = [&](int kb, auto stage_tag) {
-        constexpr int S = decltype(stage_tag)::value;
-        const uint8_t* st = smem + S * STAGE;
-        const uint8_t* nst = smem + (S ^ 1) * STAGE;
-        f32x4 un[FN];
-        if constexpr (ROWSB) {
+        // One K-step from LDS stage S.  The instruction order is pinned by hand:
+        // the MFMA of sub-tile s is issued, then the four FMAs that fold sub-tile
+        // s-D into the accumulators, so the vector ALU works in the shadow of the
+        // matrix pipe.  The empty asm statements only tie values to program points
+        // (they emit nothing); without them the compiler gathers all MFMAs first
+        // and all FMAs last.  The loads of K-step kb+1 are spread over the
+        // sub-tiles before the barrier (into the stage the previous barrier freed).
+        constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
+        constexpr int SPREAD = (NSUB - FN) / C::LPT;       // sub-tiles between two load instructions
+        static_assert(SPREAD >= 1, "not enough sub-tiles to spread the loads over");
+        auto kstep = [&](int kb, auto stage_tag) {
+            constexpr int S = decltype(stage_tag)::value;
+            const uint8_t* st = smem + S * STAGE;
+            const uint8_t* nst = smem + (S ^ 1) * STAGE;
+            f32x4 un[FN];
+            if constexpr (ROWSB) {
 #pragma unroll
-            for (int i = 0; i < FN; ++i)
-                un[i] = *reinterpret_cast<const f32x4*>(sbrow_s + S * NT + wn * C::TN + i * 16 + g4 * 4);
-        }
-        f32x4 part[D + 1];
+                for (int i = 0; i < FN; ++i)
+                    un[i] = *reinterpret_cast<const f32x4*>(sbrow_s + S * NT + wn * C::TN + i * 16 + g4 * 4);
+            }
+            f32x4 part[D + 1];
 #pragma unroll
-        for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float tjn[FM];                                  // scale products of the next K-step
-        const unsigned koff2 = kb + 2 < KB ? (unsigned)(kb + 2) << 7 : kOobOffset;
-        __builtin_amdgcn_sched_barrier(0);
+            for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+            float tjn[FM];                                  // scale products of the next K-step
+            const unsigned koff1 = kb + 1 < KB ? (unsigned)(kb + 1) << 7 : kOobOffset;
+            load_scales(cur, min(kb + 1, KB - 1));
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < NSUB + D; ++s) {
-            if (s == NSUB - FN) {
-                // Everything this wave reads from stage S is in registers.  After the
-                // barrier stage S^1 is complete and stage S may be overwritten.
-                commit_scales(S ^ 1);
-                __syncthreads();
-                load_scales(min(kb + 2, KB - 1));
+            for (int s = 0; s < NSUB + D; ++s) {
+                if (s == NSUB - FN) {
+                    // Everything this wave reads from stage S is in registers.  After the
+                    // barrier stage S^1 is complete and stage S may be overwritten.
+                    commit_scales(S ^ 1);
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (s < NSUB - FN && s % SPREAD == SPREAD - 1 && s / SPREAD < C::LPT) issue_load(cur, s / SPREAD, S ^ 1, koff1);
+                if (s < NSUB) {
+                    const int j = s / FN, i = s % FN;
+                    if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
+                    part[s % (D + 1)] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        pf[i], qf[j & 1], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+                    if (j == FM - 1) {
+                        // last activation fragment: refill this weight fragment for the next K-step
+                        pf[i] = load_frag(nst + p_base + i * 2048);
+                        if (i == FN - 1) {
+                            qf[0] = load_frag(nst + q_base);
+                            read_tj(S ^ 1, sb_n, tjn);
+                            if constexpr (!ROWSB) sb_n = cur.sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
+                        }
+                    }
+                }
+                if (s >= D) {
+                    const int ps = s - D, j = ps / FN, i = ps % FN;
+                    // the MFMA just issued comes before the FMAs of sub-tile ps
+                    if (s < NSUB) asm volatile("" : "+v"(part[s % (D + 1)]), "+v"(part[ps % (D + 1)]));
+                    const f32x4 pr = part[ps % (D + 1)];
+                    f32x4 a = acc[i][j];
+                    if constexpr (ROWSB) {
+                        a.x = __builtin_fmaf(pr.x, tj[j] * un[i].x, a.x);
+                        a.y = __builtin_fmaf(pr.y, tj[j] * un[i].y, a.y);
+                        a.z = __builtin_fmaf(pr.z, tj[j] * un[i].z, a.z);
+                        a.w = __builtin_fmaf(pr.w, tj[j] * un[i].w, a.w);
+                    } else {
+                        a.x = __builtin_fmaf(pr.x, tj[j], a.x);
+                        a.y = __builtin_fmaf(pr.y, tj[j], a.y);
+                        a.z = __builtin_fmaf(pr.z, tj[j], a.z);
+                        a.w = __builtin_fmaf(pr.w, tj[j], a.w);
+                    }
+                    asm volatile("" : "+v"(a));              // the four FMAs are done by here
+                    acc[i][j] = a;
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (s < NSUB) {
-                const int j = s / FN, i = s % FN;
-                if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
-                part[s % (D + 1)] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                    pf[i], qf[j & 1], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-                if (j == FM - 1) {
-                    // last activation fragment: refill this weight fragment for the next
-                    // K-step and push the loads of K-step kb+2 into the freed stage
-                    pf[i] = load_frag(nst + p_base + i * 2048);
-                    if (2 * i < C::LPT) issue_load(2 * i, S, koff2);
-                    if (2 * i + 1 < C::LPT) issue_load(2 * i + 1, S, koff2);
-                    if (i == FN - 1) {
-                        qf[0] = load_frag(nst + q_base);
-                        read_tj(S ^ 1, sb_n, tjn);
-                        if constexpr (!ROWSB) sb_n = sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
-                    }
-                }
-            }
-            if (s >= D) {
-                const int ps = s - D, j = ps / FN, i = ps % FN;
-                // the MFMA just issued comes before the FMAs of sub-tile ps
-                if (s < NSUB) asm volatile("" : "+v"(part[s % (D + 1)]), "+v"(part[ps % (D + 1)]));
-                const f32x4 pr = part[ps % (D + 1)];
-                f32x4 a = acc[i][j];
-                if constexpr (ROWSB) {
-                    a.x = __builtin_fmaf(pr.x, tj[j] * un[i].x, a.x);
-                    a.y = __builtin_fmaf(pr.y, tj[j] * un[i].y, a.y);
-                    a.z = __builtin_fmaf(pr.z, tj[j] * un[i].z, a.z);
-                    a.w = __builtin_fmaf(pr.w, tj[j] * un[i].w, a.w);
-                } else {
-                    a.x = __builtin_fmaf(pr.x, tj[j], a.x);
-                    a.y = __builtin_fmaf(pr.y, tj[j], a.y);
-                    a.z = __builtin_fmaf(pr.z, tj[j], a.z);
-                    a.w = __builtin_fmaf(pr.w, tj[j], a.w);
-                }
-                asm volatile("" : "+v"(a));              // the four FMAs are done by here
-                acc[i][j] = a;
-            }
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
+        };
+
+        using st0 = std::integral_constant<int, 0>;
+        using st1 = std::integral_constant<int, 1>;
+        int kb = 0;
+        for (; kb + 1 < KB; kb += 2) {
+            kstep(kb, st0{});
+            kstep(kb + 1, st1{});
         }
-#pragma unroll
-        for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
-    };
+        if (kb < KB) kstep(kb, st0{});
+        __syncthreads();                               // every wave is done with both code stages
 
-    using st0 = std::integral_constant<int, 0>;
-    using st1 = std::integral_constant<int, 1>;
-    int kb = 0;
-    for (; kb + 1 < KB; kb += 2) {
-        kstep(kb, st0{});
-        kstep(kb + 1, st1{});
-    }
-    if (kb < KB) kstep(kb, st0{});
+        // ---- the next tile's first K-step flies into stage 0 during this tile's epilogue ----
+        TileCtx nxt;
+        local += nslots;
+        const bool more = setup_tile(local, nxt);
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < C::LPT; ++i) issue_load(nxt, i, 0, 0u);
+            load_scales(nxt, 0);
+        }
 
-    // ---- epilogue: lane owns activation row m and, per weight fragment, 4 consecutive n ----
-    constexpr int ESZ = OUT_BF16 ? 2 : 4;
-    uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
+        // ---- epilogue ------------------------------------------------------------------
+        // A lane owns one activation row m and, per weight fragment, 4 consecutive n:
+        // stored directly that would be 8-byte pieces scattered over 16 rows.  Each
+        // wave instead transposes 16 rows x TN columns at a time through a private
+        // LDS strip in stage 1 and writes 16 bytes per lane, a full 128-byte (BF16)
+        // or 256-byte (FP32) row segment per group of lanes.
+        constexpr int ESZ = OUT_BF16 ? 2 : 4;
+        constexpr int SEG = C::TN * ESZ;                   // bytes of one output row segment of this wave
+        constexpr int ROWB = SEG + 16;                     // padded LDS row
+        constexpr int CPR = SEG / 16;                      // 16-byte chunks per row segment
+        constexpr int PASSES = 16 * CPR / 64;              // 64 lanes move 16 rows x CPR chunks
+        static_assert(16 * CPR % 64 == 0, "epilogue mapping");
+        static_assert((NT / 64) * 16 * ROWB <= STAGE, "epilogue strips fit in one code stage");
+        uint8_t* strip = smem + STAGE + wave * (16 * ROWB);
+        uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
+        const int n_w0 = wn * C::TN;                       // first column of this wave inside the tile
 #pragma unroll
-    for (int j = 0; j < FM; ++j) {
-        const int ml = wm * C::TM + j * 16 + l16;
-        if (ml >= m_rows) continue;
-        uint8_t* crow = c_base + ((int64_t)(m0 + ml) * p.ldc + n0) * ESZ;
+        for (int j = 0; j < FM; ++j) {
 #pragma unroll
-        for (int i = 0; i < FN; ++i) {
-            const int nl = wn * C::TN + i * 16 + g4 * 4;
-            if (nl >= n_rows) continue;
-            const f32x4 v = acc[i][j];
-            if (nl + 4 <= n_rows) {
-                if constexpr (OUT_BF16) {
-                    *reinterpret_cast<u32x2*>(crow + nl * 2) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
-                } else {
-                    f32x4* dst = reinterpret_cast<f32x4*>(crow + nl * 4);
-                    f32x4 o = v;
-                    if (p.accumulate) { const f32x4 old = *dst; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
-                    *dst = o;
-                }
-            } else {
-                const float e[4] = {v.x, v.y, v.z, v.w};
-                for (int q = 0; q < 4 && nl + q < n_rows; ++q) {
+            for (int i = 0; i < FN; ++i) {
+                const f32x4 v = acc[i][j];
+                uint8_t* dst = strip + l16 * ROWB + (i * 16 + g4 * 4) * ESZ;
+                if constexpr (OUT_BF16) *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+                else *reinterpret_cast<f32x4*>(dst) = v;
+            }
+            __builtin_amdgcn_wave_barrier();               // same-wave LDS accesses complete in order
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int idx = ps * 64 + lane;
+                const int r = idx / CPR, ch = idx % CPR;
+                const int ml = wm * C::TM + j * 16 + r;
+                const int nl = n_w0 + ch * (16 / ESZ);     // first column of this chunk inside the tile
+                const u32x4 w = *reinterpret_cast<const u32x4*>(strip + r * ROWB + ch * 16);
+                if (ml >= cur.m_rows || nl >= cur.n_rows) continue;
+                uint8_t* gp = c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ;
+                if (nl + 16 / ESZ <= cur.n_rows) {
                     if constexpr (OUT_BF16) {
-                        reinterpret_cast<uint16_t*>(crow)[nl + q] = (uint16_t)f32_to_bf16_rne(e[q]);
+                        *reinterpret_cast<u32x4*>(gp) = w;
                     } else {
-                        float* dst = reinterpret_cast<float*>(crow) + nl + q;
-                        *dst = p.accumulate ? *dst + e[q] : e[q];
+                        f32x4 o = f32x4{as_f32(w.x), as_f32(w.y), as_f32(w.z), as_f32(w.w)};
+                        if (p.accumulate) {
+                            const f32x4 old = *reinterpret_cast<const f32x4*>(gp);
+                            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+                        }
+                        *reinterpret_cast<f32x4*>(gp) = o;
+                    }
+                } else {
+                    const unsigned int wd[4] = {w.x, w.y, w.z, w.w};
+                    for (int q = 0; q < 16 / ESZ && nl + q < cur.n_rows; ++q) {
+                        if constexpr (OUT_BF16) {
+                            reinterpret_cast<uint16_t*>(gp)[q] = (uint16_t)(wd[q >> 1] >> (16 * (q & 1)));
+                        } else {
+                            float* d = reinterpret_cast<float*>(gp) + q;
+                            *d = p.accumulate ? *d + as_f32(wd[q]) : as_f32(wd[q]);
+                        }
                     }
                 }
             }
+            __builtin_amdgcn_wave_barrier();               // reads of the strip precede the next round of writes
         }
+        if (!more) break;
+        cur = nxt;
     }
 }
 
 // ---- host side -------------------------------------------------------------------
+// Compute units of the current device, rounded down to a multiple of 8 (cached per device).
+static int num_cus_x8() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cached[dev] = n / 8 * 8;
+    }
+    return cached[dev];
+}
+
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
 static ds3_status launch_one(GemmParams p, hipStream_t st) {
     if (GROUPED) p.tiles_m = (p.M + C::BM - 1) / C::BM + p.G;
@@ -337,7 +405,10 @@ static ds3_status launch_one(GemmParams p, hipStream_t st) {
     // 32-bit byte offsets inside one tile's rows, all below the out-of-range marker
     if ((int64_t)(C::BN + 1) * p.ldb + p.K >= (1ll << 31) || (int64_t)(C::BM + 1) * p.lda + p.K >= (1ll << 31))
         return DS3_ERR_UNSUPPORTED;
-    const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
+    // Persistent launch: one workgroup per compute unit (fewer if there are fewer
+    // tiles), a multiple of 8 so that every XCD gets the same number.
+    const int64_t want = ((ntiles + 7) / 8) * 8;
+    const unsigned grid = (unsigned)(want < num_cus_x8() ? want : num_cus_x8());
     gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
