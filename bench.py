@@ -124,7 +124,7 @@ def cpu_baseline(wl):
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import ds3_oracle as orc
-    ms, ns, k = 512, 4608, wl.HIDDEN
+    ms, ns, k = 1024, 9216, wl.HIDDEN
     x = wl.cfg2_x(m=ms)
     w = wl.cfg2_w(n=ns)
     t0 = time.perf_counter()

@@ -145,7 +145,7 @@ ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K,
  *   c   [total_rows][ldc] BF16 or FP32
  *   group_offsets  DEVICE array of G+1 int32, nondecreasing, [0] == 0 and
  *                  [G] <= total_rows; it is read on the device only.
- * Rows at or beyond group_offsets[G] are left untouched.
+ * Rows at or beyond group_offsets[G] are left untouched.  G <= 1023.
  */
 ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows,
                                    int64_t N, int64_t K,

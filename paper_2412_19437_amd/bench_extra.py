@@ -1,0 +1,175 @@
+"""Benchmark workloads beyond the headline one (bench.py --workload cfg3|cfg4|cfg5).
+
+Each builder returns (step, kernels, flops_per_step, config, dominant_kernel)
+with the same meaning as bench.build_cfg2: `step(record)` enqueues one pass of
+the workload on the current stream, timing every kernel with HIP events when
+`record` is set.  Inputs are synthetic, seeded and resident in HBM.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PEAK_FP8_TFLOPS = 5000.0
+PEAK_HBM_GBS = 8000.0
+
+
+def _timed():
+    from bench import Timed
+    return Timed
+
+
+def _quant_bytes(rows, cols, groups):
+    return rows * cols * 3 + groups * 4
+
+
+def build(workload, ds3, torch, wl, dev, variant):
+    return {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](ds3, torch, wl, dev, variant)
+
+
+def _bf16(torch, x, dev):
+    return torch.from_numpy(x).to(dev).to(torch.bfloat16)
+
+
+def _cfg3(ds3, torch, wl, dev, variant):
+    """MoE expert FFN forward of one GPU's 32 experts: quant 1x128 -> grouped
+    gate|up GEMM -> SwiGLU -> quant 1x128 -> grouped down GEMM."""
+    Timed = _timed()
+    G, H, I = wl.LOCAL_EXPERTS, wl.HIDDEN, wl.MOE_INTER
+    sizes, off, _ = wl.cfg3_routing()
+    rows = int(off[-1])
+    x = _bf16(torch, wl.cfg3_tokens(rows), dev)
+    gen = torch.Generator(device=dev).manual_seed(wl.seed_for(3, 2))
+    w13 = (torch.randn((G * 2 * I, H), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+    w2 = (torch.randn((G * H, I), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+    offd = torch.from_numpy(off).to(dev)
+    q13, s13 = ds3.ds3_quant_w_128x128(w13)
+    q2, s2 = ds3.ds3_quant_w_128x128(w2)
+    q13v, s13v = q13.view(G, 2 * I, H), s13.view(G, 2 * I // 128, H // 128)
+    q2v, s2v = q2.view(G, H, I), s2.view(G, H // 128, I // 128)
+    st = {}
+
+    def quant_x():
+        st["qx"], st["sx"] = ds3.ds3_quant_act_1x128(x)
+
+    def quant_w():
+        ds3.ds3_quant_w_128x128(w13)
+        ds3.ds3_quant_w_128x128(w2)
+
+    def gemm1():
+        st["h"] = ds3.ds3_grouped_gemm_fp8_bs(st["qx"], st["sx"], offd, q13v, s13v, variant=variant)
+
+    def swiglu():
+        st["act"] = ds3.ds3_swiglu(st["h"])
+
+    def quant_h():
+        st["qh"], st["sh"] = ds3.ds3_quant_act_1x128(st["act"])
+
+    def gemm2():
+        st["y"] = ds3.ds3_grouped_gemm_fp8_bs(st["qh"], st["sh"], offd, q2v, s2v, variant=variant)
+
+    f1, f2 = 2.0 * rows * 2 * I * H, 2.0 * rows * H * I
+    wbytes = _quant_bytes(G * 2 * I, H, G * 2 * I * H // 16384) + _quant_bytes(G * H, I, G * H * I // 16384)
+    kernels = [
+        Timed("quant_act_1x128(x)", quant_x, "GB/s", _quant_bytes(rows, H, rows * H // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_w_128x128(w13,w2)", quant_w, "GB/s", wbytes / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("grouped_gemm_fp8_bs(gate|up)", gemm1, "TFLOP/s", f1 / 1e12, "mfma", PEAK_FP8_TFLOPS),
+        Timed("swiglu", swiglu, "GB/s", rows * I * 6 / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_act_1x128(h)", quant_h, "GB/s", _quant_bytes(rows, I, rows * I // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("grouped_gemm_fp8_bs(down)", gemm2, "TFLOP/s", f2 / 1e12, "mfma", PEAK_FP8_TFLOPS),
+    ]
+
+    def step(record):
+        for k in kernels:
+            k(record)
+
+    cfg = {"workload": "cfg3: MoE grouped Fprop, 32 local experts of 256, 8192 tokens top-8 (sigmoid affinity + bias), "
+                       "gate|up [n_e x 7168]x[4096x7168]^T, SwiGLU, down [n_e x 2048]x[7168x2048]^T, BF16 out",
+           "rows": rows, "group_sizes_min_med_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
+           "gemm_variant": variant}
+    return step, kernels, f1 + f2, cfg, "grouped_gemm_fp8_bs(gate|up)"
+
+
+def _cfg4(ds3, torch, wl, dev, variant):
+    """Backward of the dense FFN up-projection: Dgrad dX = dY W and Wgrad dW += dY^T X."""
+    Timed = _timed()
+    M, N, K = 4096, wl.DENSE_INTER, wl.HIDDEN
+    x = _bf16(torch, wl.cfg2_x(), dev)
+    dy = _bf16(torch, wl.cfg4_dy(), dev)
+    wt = _bf16(torch, np.ascontiguousarray(wl.cfg2_w().T), dev)          # W^T [K][N]: the Dgrad weight operand
+    dw = torch.zeros((N, K), dtype=torch.float32, device=dev)
+    st = {}
+
+    def q_dy_row():
+        st["qdy"], st["sdy"] = ds3.ds3_quant_act_1x128(dy)
+
+    def q_wt():
+        st["qwt"], st["swt"] = ds3.ds3_quant_w_128x128(wt)
+
+    def dgrad():
+        st["dx"] = ds3.ds3_gemm_fp8_bs(st["qdy"], st["sdy"], st["qwt"], st["swt"], variant=variant)
+
+    def q_dy_col():
+        st["qdyt"], st["sdyt"] = ds3.ds3_quant_act_128x1(dy)
+
+    def q_x_col():
+        st["qxt"], st["sxt"] = ds3.ds3_quant_act_128x1(x)
+
+    def wgrad():
+        ds3.ds3_gemm_fp8_bs(st["qdyt"], st["sdyt"], st["qxt"], st["sxt"], sb_mode=ds3.DS3_BSCALE_PER_ROW, c=dw,
+                            accumulate=True, variant=variant)
+
+    fl = 2.0 * M * N * K
+    kernels = [
+        Timed("quant_act_1x128(dY)", q_dy_row, "GB/s", _quant_bytes(M, N, M * N // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_w_128x128(W^T)", q_wt, "GB/s", _quant_bytes(K, N, K * N // 16384) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("gemm_fp8_bs(dgrad)", dgrad, "TFLOP/s", fl / 1e12, "mfma", PEAK_FP8_TFLOPS),
+        Timed("quant_act_128x1(dY)", q_dy_col, "GB/s", _quant_bytes(M, N, M * N // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_act_128x1(X)", q_x_col, "GB/s", _quant_bytes(M, K, M * K // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("gemm_fp8_bs(wgrad, fp32 accumulate)", wgrad, "TFLOP/s", fl / 1e12, "mfma", PEAK_FP8_TFLOPS),
+    ]
+
+    def step(record):
+        for k in kernels:
+            k(record)
+
+    cfg = {"workload": "cfg4: backward of the cfg2 layer; Dgrad dX[4096x7168] = dY[4096x18432] W (dY 1x128, W^T 128x128) "
+                       "and Wgrad dW[18432x7168] += dY^T X over 4096 tokens (both operands 128x1), dW FP32",
+           "M": M, "N": N, "K": K, "gemm_variant": variant}
+    return step, kernels, 2 * fl, cfg, "gemm_fp8_bs(dgrad)"
+
+
+def _cfg5(ds3, torch, wl, dev, variant):
+    """The four MLA projections (Section 2.1.1) at 8192 tokens."""
+    Timed = _timed()
+    kernels, flops = [], 0.0
+    for idx, (name, m, n, k) in enumerate(wl.cfg5_shapes()):
+        gen = torch.Generator(device=dev).manual_seed(wl.seed_for(5, idx))
+        x = torch.randn((m, k), generator=gen, device=dev).to(torch.bfloat16)
+        w = (torch.randn((n, k), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        st = {}
+
+        def qx(x=x, st=st):
+            st["qa"], st["sa"] = ds3.ds3_quant_act_1x128(x)
+
+        def qw(w=w, st=st):
+            st["qb"], st["sb"] = ds3.ds3_quant_w_128x128(w)
+
+        def gemm(st=st):
+            st["y"] = ds3.ds3_gemm_fp8_bs(st["qa"], st["sa"], st["qb"], st["sb"], variant=variant)
+
+        fl = 2.0 * m * n * k
+        flops += fl
+        kernels += [
+            Timed(f"quant_act_1x128({name})", qx, "GB/s", _quant_bytes(m, k, m * k // 128) / 1e9, "hbm", PEAK_HBM_GBS),
+            Timed(f"quant_w_128x128({name})", qw, "GB/s", _quant_bytes(n, k, n * k // 16384 + 1) / 1e9, "hbm", PEAK_HBM_GBS),
+            Timed(f"gemm_fp8_bs({name} {m}x{n}x{k})", gemm, "TFLOP/s", fl / 1e12, "mfma", PEAK_FP8_TFLOPS),
+        ]
+
+    def step(record):
+        for kk in kernels:
+            kk(record)
+
+    cfg = {"workload": "cfg5: MLA projections at 8192 tokens: q_a 7168->1536, kv_a 7168->576, q_b 1536->24576, "
+                       "kv_b 512->32768; quant 1x128 + quant 128x128 + block-scaled FP8 GEMM each, BF16 out",
+           "gemm_variant": variant}
+    return step, kernels, flops, cfg, "gemm_fp8_bs(q_b 8192x24576x1536)"

@@ -40,7 +40,7 @@ ds3_status gemm_common(int variant, int32_t G, const int32_t* offs, int64_t M, i
     if (!a || !b || !sa || !sb || !c) return DS3_ERR_NULL;
     if (G > 0 && !offs) return DS3_ERR_NULL;
     if (lda < K || ldb < K || ldc < N) return DS3_ERR_SHAPE;
-    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || G > 65536) return DS3_ERR_UNSUPPORTED;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || G > 1023) return DS3_ERR_UNSUPPORTED;
     if (!aligned16(a) || !aligned16(b) || !aligned16(c) || lda % 16 || ldb % 16 || ldc % 4) return DS3_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DS3_ERR_ALIGN;
     GemmParams p{};

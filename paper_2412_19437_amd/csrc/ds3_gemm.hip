@@ -35,9 +35,12 @@ namespace ds3 {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-template <int BN_, int BM_, int WN_, int WM_>
+constexpr int kMaxGroups = 1023;                       // experts per grouped call (prefix table in LDS)
+
+template <int BN_, int BM_, int WN_, int WM_, int NS_>
 struct Cfg {
     static constexpr int BN = BN_, BM = BM_, WN = WN_, WM = WM_;
+    static constexpr int NS = NS_;                     // LDS stages: loads run NS-1 K-steps ahead of the MFMAs
     static constexpr int NT = 64 * WN * WM;
     static constexpr int TN = BN / WN, TM = BM / WM;   // wave tile
     static constexpr int FN = TN / 16, FM = TM / 16;   // 16-row fragments per wave
@@ -46,12 +49,17 @@ struct Cfg {
     static constexpr int STAGE = ROWS * 128;           // bytes of codes per K-step
     static constexpr int RPI = NT / 8;                 // tile rows one load instruction of the workgroup covers
     static constexpr int LPT = ROWS / RPI;             // 16-byte loads per thread per K-step
-    static constexpr int LDS_BYTES = 2 * STAGE + 4 * NT * 4;   // codes + [2][NT] sa + [2][NT] per-row sb
+    static constexpr int SCALE_BYTES = 2 * NS * NT * 4;        // [NS][NT] sa + [NS][NT] per-row sb
+    static constexpr int LDS_BYTES = NS * STAGE + SCALE_BYTES + (kMaxGroups + 1) * 4;   // + row-tile prefix of the experts
+    // workgroups that fit one compute unit: 160 KiB of LDS, and two waves per SIMD (the
+    // kernels need more than 128 registers per lane)
+    static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (512 / NT) ? (160 * 1024 / LDS_BYTES) : (512 / NT);
     static_assert(ROWS % RPI == 0 && BN % RPI == 0 && RPI % 16 == 0, "load mapping");
     static_assert(BM <= NT && BN <= NT, "scale staging uses one thread per row");
     static_assert(TN <= 128 && 128 % TN == 0, "one weight-scale block per wave");
     static_assert(FM % 2 == 0 && FM >= 2, "activation fragments are double-buffered");
     static_assert(LPT <= 2 * FN, "loads are interleaved with the last fragment's MFMAs");
+    static_assert(NS == 2 || NS == 3, "stage ring");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -76,8 +84,9 @@ template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
     constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE, NSUB = C::NSUB;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[C::LDS_BYTES];
-    float* const sa_s = reinterpret_cast<float*>(smem + 2 * STAGE);            // [2][NT], first BM used
-    float* const sbrow_s = sa_s + 2 * NT;                                      // [2][NT], first BN used (per-row mode)
+    constexpr int NS = C::NS;
+    float* const sa_s = reinterpret_cast<float*>(smem + NS * STAGE);           // [NS][NT], first BM used
+    float* const sbrow_s = sa_s + NS * NT;                                     // [NS][NT], first BN used (per-row mode)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -90,7 +99,22 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     // Workgroup b runs on XCD b % 8.  The tile list is cut into 8 contiguous
     // chunks, one per XCD; the workgroups of an XCD take consecutive tiles of
     // their chunk, so the tiles in flight on one L2 form a compact panel.
-    const int ntiles = p.tiles_m * p.tiles_n;
+    int tiles_m = p.tiles_m;
+    int* const gpre = reinterpret_cast<int*>(smem + NS * STAGE + C::SCALE_BYTES);   // [G+1] row tiles before expert g
+    if constexpr (GROUPED) {
+        // the host only knows an upper bound on the row tiles; build their prefix over the experts
+        if (tid == 0) {
+            int cum = 0;
+            for (int g = 0; g < p.G; ++g) {
+                gpre[g] = cum;
+                cum += (min(p.group_offsets[g + 1], p.M) - min(p.group_offsets[g], p.M) + BM - 1) / BM;
+            }
+            gpre[p.G] = cum;
+        }
+        __syncthreads();
+        tiles_m = gpre[p.G];
+    }
+    const int ntiles = tiles_m * p.tiles_n;
     const int per_xcd = (ntiles + 7) >> 3;
     const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslots = (int)(gridDim.x >> 3);
 
@@ -102,24 +126,26 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             constexpr int PM = 4;                      // tiles of M per panel
             const int panel = PM * p.tiles_n;
             const int pi = t / panel, r = t - pi * panel;
-            const int pm = min(PM, p.tiles_m - pi * PM);
+            const int pm = min(PM, tiles_m - pi * PM);
             m0 = (pi * PM + r % pm) * BM;
             n0 = (r / pm) * BN;
             m_end = p.M;
         } else {
-            const int mt = t / p.tiles_n;
-            n0 = (t - mt * p.tiles_n) * BN;
-            int cum = 0, lo = p.group_offsets[0];
-            m0 = -1; m_end = 0;
-            for (int g = 0; g < p.G; ++g) {
-                const int hi = p.group_offsets[g + 1];
-                const int nt_g = (hi - lo + BM - 1) / BM;
-                if (m0 < 0 && mt < cum + nt_g) { grp = g; m0 = lo + (mt - cum) * BM; m_end = hi; }
-                cum += nt_g;
-                lo = hi;
+            // Tiles are ordered expert by expert, then by column tile, the expert's row
+            // tiles innermost: the workgroups of an XCD that run side by side share one
+            // weight tile through the L2, and every expert's weights are streamed once.
+            int lo = 0, hi = p.G;                      // largest g with gpre[g] * tiles_n <= t
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (gpre[mid] * p.tiles_n <= t) lo = mid; else hi = mid;
             }
-            if (m0 < 0) return false;                  // past the last expert: tiles are ordered, nothing follows
-            m_end = min(m_end, p.M);
+            grp = lo;
+            const int nt_g = gpre[grp + 1] - gpre[grp];
+            const int r = t - gpre[grp] * p.tiles_n;
+            n0 = (r / nt_g) * BN;
+            const int row_lo = min(p.group_offsets[grp], p.M);
+            m0 = row_lo + (r % nt_g) * BM;
+            m_end = min(p.group_offsets[grp + 1], p.M);
         }
         c.m0 = m0; c.n0 = n0;
         c.m_rows = min(m_end - m0, BM);                // valid rows of this tile (>= 1)
@@ -195,13 +221,29 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     TileCtx cur;
     int local = slot;
     if (!setup_tile(local, cur)) return;
-    // K-step 0 of the first tile into stage 0
+    // Workgroup barrier that lets the newest `pending` vector-memory operations of this
+    // wave stay in flight (the loads that run more than one K-step ahead); LDS
+    // operations are all complete when it returns.
+    auto barrier_keep = [&](auto pending_tag) {
+        constexpr int pending = decltype(pending_tag)::value;
+        static_assert(pending >= 0 && pending < 16, "vmcnt immediate");
+        asm volatile("" ::: "memory");                 // the compiler moves no memory access across
+        __builtin_amdgcn_s_waitcnt(pending | 0x70);    // vmcnt(pending) lgkmcnt(0), expcnt untouched
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // the first NS-1 K-steps of the first tile into stages 0 .. NS-2
+    auto issue_first_steps = [&](const TileCtx& c) {
 #pragma unroll
-    for (int i = 0; i < C::LPT; ++i) issue_load(cur, i, 0, 0u);
-    load_scales(cur, 0);
+        for (int ks = 0; ks < NS - 1; ++ks)
+#pragma unroll
+            for (int i = 0; i < C::LPT; ++i) issue_load(c, i, ks, ks < KB ? (unsigned)ks << 7 : kOobOffset);
+        load_scales(c, 0);
+    };
+    issue_first_steps(cur);
 
     for (;;) {
-        // ---- entry: K-step 0 of `cur` is in flight into stage 0, its scales are in registers ----
+        // ---- entry: K-steps 0 .. NS-2 of `cur` are in flight into stages 0 .. NS-2, the scales of K-step 0 are in registers ----
         commit_scales(0);
         __syncthreads();
         float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
@@ -230,7 +272,9 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         auto kstep = [&](int kb, auto stage_tag) {
             constexpr int S = decltype(stage_tag)::value;
             const uint8_t* st = smem + S * STAGE;
-            const uint8_t* nst = smem + (S ^ 1) * STAGE;
+            constexpr int SN = (S + 1) % NS;                // stage of the next K-step
+            constexpr int SL = (S + NS - 1) % NS;           // stage this K-step's loads fill (K-step kb+NS-1)
+            const uint8_t* nst = smem + SN * STAGE;
             f32x4 un[FN];
             if constexpr (ROWSB) {
 #pragma unroll
@@ -241,19 +285,19 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 #pragma unroll
             for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
             float tjn[FM];                                  // scale products of the next K-step
-            const unsigned koff1 = kb + 1 < KB ? (unsigned)(kb + 1) << 7 : kOobOffset;
+            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
             load_scales(cur, min(kb + 1, KB - 1));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < NSUB + D; ++s) {
                 if (s == NSUB - FN) {
                     // Everything this wave reads from stage S is in registers.  After the
-                    // barrier stage S^1 is complete and stage S may be overwritten.
-                    commit_scales(S ^ 1);
-                    __syncthreads();
+                    // barrier the next stage is complete and stage S may be overwritten.
+                    commit_scales(SN);
+                    barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (s < NSUB - FN && s % SPREAD == SPREAD - 1 && s / SPREAD < C::LPT) issue_load(cur, s / SPREAD, S ^ 1, koff1);
+                if (s < NSUB - FN && s % SPREAD == SPREAD - 1 && s / SPREAD < C::LPT) issue_load(cur, s / SPREAD, SL, koff1);
                 if (s < NSUB) {
                     const int j = s / FN, i = s % FN;
                     if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
@@ -264,7 +308,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                         pf[i] = load_frag(nst + p_base + i * 2048);
                         if (i == FN - 1) {
                             qf[0] = load_frag(nst + q_base);
-                            read_tj(S ^ 1, sb_n, tjn);
+                            read_tj(SN, sb_n, tjn);
                             if constexpr (!ROWSB) sb_n = cur.sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
                         }
                     }
@@ -297,29 +341,36 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 
         using st0 = std::integral_constant<int, 0>;
         using st1 = std::integral_constant<int, 1>;
+        using st2 = std::integral_constant<int, 2>;
         int kb = 0;
-        for (; kb + 1 < KB; kb += 2) {
-            kstep(kb, st0{});
-            kstep(kb + 1, st1{});
+        if constexpr (NS == 2) {
+            for (; kb + 1 < KB; kb += 2) {
+                kstep(kb, st0{});
+                kstep(kb + 1, st1{});
+            }
+            if (kb < KB) kstep(kb, st0{});
+        } else {
+            for (; kb + 2 < KB; kb += 3) {
+                kstep(kb, st0{});
+                kstep(kb + 1, st1{});
+                kstep(kb + 2, st2{});
+            }
+            if (kb < KB) kstep(kb, st0{});
+            if (kb + 1 < KB) kstep(kb + 1, st1{});
         }
-        if (kb < KB) kstep(kb, st0{});
-        __syncthreads();                               // every wave is done with both code stages
+        __syncthreads();                               // every wave is done with all code stages
 
-        // ---- the next tile's first K-step flies into stage 0 during this tile's epilogue ----
+        // ---- the next tile's first K-steps fly into stages 0 .. NS-2 during this tile's epilogue ----
         TileCtx nxt;
         local += nslots;
         const bool more = setup_tile(local, nxt);
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < C::LPT; ++i) issue_load(nxt, i, 0, 0u);
-            load_scales(nxt, 0);
-        }
+        if (more) issue_first_steps(nxt);
 
         // ---- epilogue ------------------------------------------------------------------
         // A lane owns one activation row m and, per weight fragment, 4 consecutive n:
         // stored directly that would be 8-byte pieces scattered over 16 rows.  Each
         // wave instead transposes 16 rows x TN columns at a time through a private
-        // LDS strip in stage 1 and writes 16 bytes per lane, a full 128-byte (BF16)
+        // LDS strip in the last stage and writes 16 bytes per lane, a full 128-byte (BF16)
         // or 256-byte (FP32) row segment per group of lanes.
         constexpr int ESZ = OUT_BF16 ? 2 : 4;
         constexpr int SEG = C::TN * ESZ;                   // bytes of one output row segment of this wave
@@ -328,7 +379,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         constexpr int PASSES = 16 * CPR / 64;              // 64 lanes move 16 rows x CPR chunks
         static_assert(16 * CPR % 64 == 0, "epilogue mapping");
         static_assert((NT / 64) * 16 * ROWB <= STAGE, "epilogue strips fit in one code stage");
-        uint8_t* strip = smem + STAGE + wave * (16 * ROWB);
+        uint8_t* strip = smem + (NS - 1) * STAGE + wave * (16 * ROWB);
         uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
         const int n_w0 = wn * C::TN;                       // first column of this wave inside the tile
 #pragma unroll
@@ -405,10 +456,11 @@ static ds3_status launch_one(GemmParams p, hipStream_t st) {
     // 32-bit byte offsets inside one tile's rows, all below the out-of-range marker
     if ((int64_t)(C::BN + 1) * p.ldb + p.K >= (1ll << 31) || (int64_t)(C::BM + 1) * p.lda + p.K >= (1ll << 31))
         return DS3_ERR_UNSUPPORTED;
-    // Persistent launch: one workgroup per compute unit (fewer if there are fewer
-    // tiles), a multiple of 8 so that every XCD gets the same number.
+    // Persistent launch: as many workgroups as fit the chip at once (fewer if there
+    // are fewer tiles), a multiple of 8 so that every XCD gets the same number.
     const int64_t want = ((ntiles + 7) / 8) * 8;
-    const unsigned grid = (unsigned)(want < num_cus_x8() ? want : num_cus_x8());
+    const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
+    const unsigned grid = (unsigned)(want < slots ? want : slots);
     gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
@@ -422,17 +474,22 @@ static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode,
     return bf16 ? launch_one<C, false, true, false>(p, st) : launch_one<C, false, false, false>(p, st);
 }
 
-int gemm_num_variants() { return 3; }
+int gemm_num_variants() { return 4; }
 
 ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
     if (variant < 0) {
-        // default choice by shape: grouped problems take the narrower M tile
-        variant = (p.G > 0) ? 1 : 0;
+        // default choice: the 256x256 tile (also the fastest for the ragged expert groups);
+        // the per-row-scale form (more live registers) takes the narrower M tile; problems with
+        // too few large tiles to fill the chip take 128x128 tiles, two workgroups per CU
+        variant = (mode == DS3_BSCALE_PER_ROW) ? 1 : 0;
+        const int64_t big = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
+        if (p.G == 0 && big * 8 < 5 * (int64_t)num_cus_x8()) variant = 2;
     }
     switch (variant) {
-        case 0: return launch_cfg<Cfg<256, 256, 4, 2>>(p, ct, mode, st);
-        case 1: return launch_cfg<Cfg<256, 128, 4, 2>>(p, ct, mode, st);
-        case 2: return launch_cfg<Cfg<128, 128, 2, 2>>(p, ct, mode, st);
+        case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>>(p, ct, mode, st);
+        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 2>>(p, ct, mode, st);
+        case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>>(p, ct, mode, st);
+        case 3: return launch_cfg<Cfg<256, 128, 4, 2, 3>>(p, ct, mode, st);
         default: return DS3_ERR_UNSUPPORTED;
     }
 }
