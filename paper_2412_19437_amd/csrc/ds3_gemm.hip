@@ -474,7 +474,7 @@ static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode,
     return bf16 ? launch_one<C, false, true, false>(p, st) : launch_one<C, false, false, false>(p, st);
 }
 
-int gemm_num_variants() { return 4; }
+int gemm_num_variants() { return 3; }
 
 ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
     if (variant < 0) {
@@ -487,9 +487,8 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
     }
     switch (variant) {
         case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>>(p, ct, mode, st);
-        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 2>>(p, ct, mode, st);
+        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 3>>(p, ct, mode, st);
         case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>>(p, ct, mode, st);
-        case 3: return launch_cfg<Cfg<256, 128, 4, 2, 3>>(p, ct, mode, st);
         default: return DS3_ERR_UNSUPPORTED;
     }
 }
