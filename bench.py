@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-variant", type=int, default=-1)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run three plain 256 MiB device copies and exit (scales the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -153,6 +155,14 @@ def main():
         sys.exit(3)
     ds3._L()                                     # fail loudly if libds3.so has not been built
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 256 << 20, "copy_bytes_written": 256 << 20, "launches": 3}))
+        return
     if args.workload != "cfg2":
         from paper_2412_19437_amd import bench_extra
         step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant)
@@ -173,7 +183,8 @@ def main():
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tfile):
-        traffic = json.load(open(tfile)).get(args.workload, {}).get(dominant)
+        entry = json.load(open(tfile)).get(args.workload, {}).get(dominant)
+        traffic = entry["total_bytes"] if entry else None     # HBM-side bytes per launch, from profiles/
     out = {
         "metric": "block-scaled FP8 GEMM TFLOP/s + % FP8 MFMA peak; quantizer GB/s + % HBM peak",
         "value": flops * args.steps / dt / 1e12,
