@@ -246,6 +246,10 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         // ---- entry: K-steps 0 .. NS-2 of `cur` are in flight into stages 0 .. NS-2, the scales of K-step 0 are in registers ----
         commit_scales(0);
         __syncthreads();
+        // the part of K-step NS-1 that a previous K-step's barrier would have issued
+#pragma unroll
+        for (int i = 0; i < (C::LPT < FN ? C::LPT : FN); ++i)
+            issue_load(cur, i, NS - 1, NS - 1 < KB ? (unsigned)(NS - 1) << 7 : kOobOffset);
         float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
         float tj[FM];
         read_tj(0, ROWSB ? 1.f : cur.sb_blk[0], tj);
@@ -264,11 +268,14 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         // s-D into the accumulators, so the vector ALU works in the shadow of the
         // matrix pipe.  The empty asm statements only tie values to program points
         // (they emit nothing); without them the compiler gathers all MFMAs first
-        // and all FMAs last.  The loads of K-step kb+1 are spread over the
-        // sub-tiles before the barrier (into the stage the previous barrier freed).
+        // and all FMAs last.
         constexpr int D = 2;                               // MFMAs in flight ahead of their FMAs
-        constexpr int SPREAD = (NSUB - FN) / C::LPT;       // sub-tiles between two load instructions
-        static_assert(SPREAD >= 1, "not enough sub-tiles to spread the loads over");
+        // The stage a barrier frees is refilled at once: the first TAILN loads of the
+        // K-step NS steps ahead go out behind the barrier, one per sub-tile of the last
+        // activation fragment, the rest at the head of the next K-step.
+        constexpr int TAILN = C::LPT < FN ? C::LPT : FN;   // loads issued right behind the barrier
+        constexpr int HEADN = C::LPT - TAILN;              // loads issued at the head of the following K-step
+        static_assert(HEADN <= NSUB - FN, "not enough sub-tiles before the barrier for the head loads");
         auto kstep = [&](int kb, auto stage_tag) {
             constexpr int S = decltype(stage_tag)::value;
             const uint8_t* st = smem + S * STAGE;
@@ -285,7 +292,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 #pragma unroll
             for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
             float tjn[FM];                                  // scale products of the next K-step
-            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
+            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;   // head loads
+            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;           // tail loads
             load_scales(cur, min(kb + 1, KB - 1));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (s < NSUB - FN && s % SPREAD == SPREAD - 1 && s / SPREAD < C::LPT) issue_load(cur, s / SPREAD, SL, koff1);
+                if (s < HEADN) issue_load(cur, TAILN + s, SL, koff1);
                 if (s < NSUB) {
                     const int j = s / FN, i = s % FN;
                     if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
@@ -306,6 +314,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     if (j == FM - 1) {
                         // last activation fragment: refill this weight fragment for the next K-step
                         pf[i] = load_frag(nst + p_base + i * 2048);
+                        if (i < TAILN) issue_load(cur, i, S, koff2);
                         if (i == FN - 1) {
                             qf[0] = load_frag(nst + q_base);
                             read_tj(SN, sb_n, tjn);
