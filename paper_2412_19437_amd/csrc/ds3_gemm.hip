@@ -117,10 +117,19 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int ntiles = tiles_m * p.tiles_n;
     const int per_xcd = (ntiles + 7) >> 3;
     const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslots = (int)(gridDim.x >> 3);
+    // A last round that would occupy at most half of the XCD's workgroups is cut into
+    // half tiles (the two M halves of a tile belong to different waves, and the waves
+    // of the missing half skip their MFMAs), so that every workgroup gets one.
+    const int tail = per_xcd % nslots;
+    const bool split_tail = !GROUPED && C::WM == 2 && per_xcd > nslots && tail > 0 && 2 * tail <= nslots && p.M % BM == 0;
+    const int n_full = split_tail ? per_xcd - tail : per_xcd;
+    const int n_virtual = split_tail ? n_full + 2 * tail : per_xcd;
 
     auto setup_tile = [&](int local, TileCtx& c) -> bool {
-        const int t = xcd * per_xcd + local;
-        if (local >= per_xcd || t >= ntiles) return false;
+        if (local >= n_virtual) return false;
+        const int half = local < n_full ? -1 : ((local - n_full) & 1);
+        const int t = xcd * per_xcd + (local < n_full ? local : n_full + ((local - n_full) >> 1));
+        if (t >= ntiles) return false;
         int m0, m_end, n0, grp = 0;
         if constexpr (!GROUPED) {
             constexpr int PM = 4;                      // tiles of M per panel
@@ -130,6 +139,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             m0 = (pi * PM + r % pm) * BM;
             n0 = (r / pm) * BN;
             m_end = p.M;
+            if (half >= 0) { m0 += half * (BM / 2); m_end = min(m_end, m0 + BM / 2); }
         } else {
             // Tiles are ordered expert by expert, then by column tile, the expert's row
             // tiles innermost: the workgroups of an XCD that run side by side share one
@@ -348,25 +358,46 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
         };
 
+        // The same K-step for a wave whose activation rows all lie beyond the tile's valid
+        // rows (ragged expert groups, half tiles): it moves its share of the data and
+        // keeps the barriers, in the same order of memory operations, but computes nothing.
+        auto kstep_idle = [&](int kb, auto stage_tag) {
+            constexpr int S = decltype(stage_tag)::value;
+            constexpr int SN = (S + 1) % NS, SL = (S + NS - 1) % NS;
+            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
+            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;
+            load_scales(cur, min(kb + 1, KB - 1));
+#pragma unroll
+            for (int i = 0; i < HEADN; ++i) issue_load(cur, TAILN + i, SL, koff1);
+            commit_scales(SN);
+            barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
+#pragma unroll
+            for (int i = 0; i < TAILN; ++i) issue_load(cur, i, S, koff2);
+        };
+
         using st0 = std::integral_constant<int, 0>;
         using st1 = std::integral_constant<int, 1>;
         using st2 = std::integral_constant<int, 2>;
-        int kb = 0;
-        if constexpr (NS == 2) {
-            for (; kb + 1 < KB; kb += 2) {
-                kstep(kb, st0{});
-                kstep(kb + 1, st1{});
+        const bool active = wm * C::TM < cur.m_rows;    // wave-uniform
+        auto kloop = [&](auto step) {
+            int kb = 0;
+            if constexpr (NS == 2) {
+                for (; kb + 1 < KB; kb += 2) {
+                    step(kb, st0{});
+                    step(kb + 1, st1{});
+                }
+                if (kb < KB) step(kb, st0{});
+            } else {
+                for (; kb + 2 < KB; kb += 3) {
+                    step(kb, st0{});
+                    step(kb + 1, st1{});
+                    step(kb + 2, st2{});
+                }
+                if (kb < KB) step(kb, st0{});
+                if (kb + 1 < KB) step(kb + 1, st1{});
             }
-            if (kb < KB) kstep(kb, st0{});
-        } else {
-            for (; kb + 2 < KB; kb += 3) {
-                kstep(kb, st0{});
-                kstep(kb + 1, st1{});
-                kstep(kb + 2, st2{});
-            }
-            if (kb < KB) kstep(kb, st0{});
-            if (kb + 1 < KB) kstep(kb + 1, st1{});
-        }
+        };
+        if (active) kloop(kstep); else kloop(kstep_idle);
         __syncthreads();                               // every wave is done with all code stages
 
         // ---- the next tile's first K-steps fly into stages 0 .. NS-2 during this tile's epilogue ----
@@ -391,6 +422,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         uint8_t* strip = smem + (NS - 1) * STAGE + wave * (16 * ROWB);
         uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
         const int n_w0 = wn * C::TN;                       // first column of this wave inside the tile
+        if (active) {
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
 #pragma unroll
@@ -434,6 +466,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 }
             }
             __builtin_amdgcn_wave_barrier();               // reads of the strip precede the next round of writes
+        }
         }
         if (!more) break;
         cur = nxt;
