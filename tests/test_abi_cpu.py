@@ -77,6 +77,7 @@ def test_gemm_rejects_bad_arguments_on_the_host(pkg):
     gg = L.ds3_grouped_gemm_fp8_bs
     assert gg(2, None, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 1
     assert gg(0, None, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 0
+    assert gg(1024, p, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 5   # more than 1023 experts
     assert L.ds3_gemm_fp8_bs_v(99, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, 1, 1, 0, p, 1, 16, 0, None, 0, None) == 5
     assert L.ds3_swiglu(p, 4, 12, 24, p, 16, None) == 3
     assert L.ds3_swiglu(None, 4, 16, 32, p, 16, None) == 1

@@ -62,7 +62,8 @@ def test_cfg1_end_to_end_all_variants(ds3):
         assert e16 <= TOL_BF16, (v, e16)
 
 
-@pytest.mark.parametrize("shape", [(256, 512, 1024), (300, 576, 256), (17, 130, 384), (1, 4, 128), (513, 260, 128)])
+@pytest.mark.parametrize("shape", [(256, 512, 1024), (300, 576, 256), (17, 130, 384), (1, 4, 128), (513, 260, 128),
+                                   (2048, 9216, 256)])   # the last one: 288 large tiles, a half-tile tail round
 def test_exactness_small_integer_codes(ds3, shape):
     """Codes in {0, +-1, +-2} and power-of-two scales in a narrow range: every product,
     partial sum and rescaled sum is exactly representable, so the FP32 output
@@ -162,6 +163,27 @@ def test_grouped_small_with_empty_and_ragged_groups(ds3):
             d = host(ds3.ds3_gemm_fp8_bs(dev(a[lo:hi]), dev(sa[lo:hi]), dev(b[gi]), dev(sb[gi]),
                                          out_dtype=torch.float32, variant=v))
             assert np.array_equal(d, c[lo:hi]), (v, gi)
+
+
+def test_grouped_many_experts_exact(ds3):
+    """40 experts with sizes from 0 to several row tiles, small-integer codes and
+    power-of-two scales: the grouped FP32 output equals the oracle bit for bit."""
+    rng = np.random.default_rng(46)
+    sizes = rng.integers(0, 700, 40)
+    sizes[[3, 17, 39]] = 0
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    total, n, k, g = int(off[-1]), 640, 256, len(sizes)
+    table = np.array([0x00, 0x38, 0x40, 0xB8, 0xC0, 0x80], dtype=np.uint8)
+    a = table[rng.integers(0, 6, (total, k))]
+    b = table[rng.integers(0, 6, (g, n, k))]
+    sa = np.ldexp(1.0, rng.integers(-2, 2, (total, k // 128))).astype(np.float32)
+    sb = np.ldexp(1.0, rng.integers(-1, 3, (g, n // 128, k // 128))).astype(np.float32)
+    ref = orc.grouped_gemm_fp8_bs(a, sa, off, b, sb)
+    for v in _variants(ds3):
+        announce(f"grouped 40 experts variant {v}")
+        c = host(ds3.ds3_grouped_gemm_fp8_bs(dev(a), _kmajor(sa), dev(off), dev(b), dev(sb), out_dtype=torch.float32,
+                                             variant=v))
+        assert np.array_equal(c.astype(np.float64), ref), v
 
 
 def test_moe_expert_ffn_scaled_down(ds3):
