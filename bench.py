@@ -126,7 +126,7 @@ def cpu_baseline(wl):
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import ds3_oracle as orc
-    ms, ns, k = 1024, 9216, wl.HIDDEN
+    ms, ns, k = 4096, wl.DENSE_INTER, wl.HIDDEN      # the whole cfg2 problem: about 10 s on the GPU machine's host
     x = wl.cfg2_x(m=ms)
     w = wl.cfg2_w(n=ns)
     t0 = time.perf_counter()
@@ -138,7 +138,7 @@ def cpu_baseline(wl):
     threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
     return {"value": 2.0 * ms * ns * k / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "seconds": dt,
-            "sample": f"first {ms} rows of X and first {ns} rows of W of cfg2: oracle quant 1x128 + quant 128x128 + "
+            "sample": f"the whole cfg2 step once: oracle quant 1x128 of X[{ms}x{k}] + quant 128x128 of W[{ns}x{k}] + "
                       f"FP64 GEMM {ms}x{ns}x{k}; numpy elementwise (1 thread) + OpenBLAS dgemm ({threads} threads)"}
 
 
