@@ -422,9 +422,27 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         uint8_t* strip = smem + (NS - 1) * STAGE + wave * (16 * ROWB);
         uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
         const int n_w0 = wn * C::TN;                       // first column of this wave inside the tile
+        // Accumulating FP32 output: the old values of fragment row group j+1 are fetched
+        // while group j is transposed and stored, so the read-modify-write does not
+        // expose one memory latency per store.
+        [[maybe_unused]] f32x4 oldv[2][PASSES];
+        auto fetch_old = [&](int j, f32x4* dstv) {
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int idx = ps * 64 + lane;
+                const int ml = wm * C::TM + j * 16 + idx / CPR;
+                const int nl = n_w0 + (idx % CPR) * (16 / ESZ);
+                dstv[ps] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (ml < cur.m_rows && nl + 16 / ESZ <= cur.n_rows)
+                    dstv[ps] = *reinterpret_cast<const f32x4*>(c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ);
+            }
+        };
+        const bool accum = !OUT_BF16 && p.accumulate;
         if (active) {
+        if constexpr (!OUT_BF16) { if (accum) fetch_old(0, oldv[0]); }
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
+            if constexpr (!OUT_BF16) { if (accum && j + 1 < FM) fetch_old(j + 1, oldv[(j + 1) & 1]); }
 #pragma unroll
             for (int i = 0; i < FN; ++i) {
                 const f32x4 v = acc[i][j];
@@ -447,8 +465,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                         *reinterpret_cast<u32x4*>(gp) = w;
                     } else {
                         f32x4 o = f32x4{as_f32(w.x), as_f32(w.y), as_f32(w.z), as_f32(w.w)};
-                        if (p.accumulate) {
-                            const f32x4 old = *reinterpret_cast<const f32x4*>(gp);
+                        if (accum) {
+                            const f32x4 old = oldv[j & 1][ps];
                             o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
                         }
                         *reinterpret_cast<f32x4*>(gp) = o;
