@@ -31,6 +31,8 @@ Readings where the paper is silent (all are repeated in the design notes):
 * An all-zero group stores s = 1 and (signed) zero codes.
 * A ragged trailing group is simply smaller.
 * Inputs must be finite.
+* Power-of-two ("round scaled", Section 3.3.3) factors: the smallest power
+  of two >= amax / 448, elements multiplied by its exact reciprocal.
 
 Pins (tests marked "not gpu"): closed form over all 256 codes, round trip of
 all finite codes, every midpoint tie, brute-force nearest-neighbour search,
@@ -97,9 +99,14 @@ def e4m3_encode_rne_sat(y) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Quantizers (Section 3.3.2, Fine-Grained Quantization / Online Quantization)
 # --------------------------------------------------------------------------
-def _quant_groups(xg: np.ndarray, axes):
+def _quant_groups(xg: np.ndarray, axes, pow2: bool = False):
     """Quantize groups.  ``xg`` is float32; the max-abs is taken over ``axes``
-    (kept as size-1 axes for broadcasting).  Returns (codes, scales)."""
+    (kept as size-1 axes for broadcasting).  Returns (codes, scales).
+
+    ``pow2`` selects the "round scaled" factors of Section 3.3.3 (integral
+    powers of two): the scale is the smallest power of two not below amax/448
+    (reading: rounded up, so that nothing exceeds the E4M3 range), and the
+    elements are multiplied by its exact reciprocal."""
     if xg.dtype != np.float32:
         raise TypeError("quantizer input must be float32 (BF16 widens exactly)")
     if not np.all(np.isfinite(xg)):
@@ -107,8 +114,15 @@ def _quant_groups(xg: np.ndarray, axes):
     amax = np.max(np.abs(xg), axis=axes, keepdims=True).astype(np.float32)
     zero = amax == np.float32(0)
     safe = np.where(zero, np.float32(1), amax)
-    s = np.where(zero, np.float32(1), safe / np.float32(E4M3_MAX)).astype(np.float32)
-    r = np.where(zero, np.float32(0), np.float32(E4M3_MAX) / safe).astype(np.float32)
+    if pow2:
+        ratio = safe.astype(np.float64) / E4M3_MAX           # exact enough: only its binade matters, ties are exact
+        m, ex = np.frexp(ratio)                              # ratio = m * 2^ex, m in [0.5, 1)
+        e = np.where(m == 0.5, ex - 1, ex)                   # smallest e with 2^e >= ratio
+        s = np.where(zero, np.float32(1), np.ldexp(1.0, e)).astype(np.float32)
+        r = np.where(zero, np.float32(0), np.ldexp(1.0, -e)).astype(np.float32)
+    else:
+        s = np.where(zero, np.float32(1), safe / np.float32(E4M3_MAX)).astype(np.float32)
+        r = np.where(zero, np.float32(0), np.float32(E4M3_MAX) / safe).astype(np.float32)
     y = (xg * r).astype(np.float32)                  # one FP32 multiply per element
     return e4m3_encode_rne_sat(y), s
 
@@ -119,7 +133,7 @@ def _pad_to(x: np.ndarray, rows: int, cols: int) -> np.ndarray:
     return out
 
 
-def quant_act_1x128(x):
+def quant_act_1x128(x, pow2: bool = False):
     """1x128 tiles: per row (token), per 128 contiguous columns (channels).
     x: float32 [M][K].  Returns codes uint8 [M][K], scales float32 [M][ceil(K/128)].
     Zero padding of a ragged last tile changes neither its max-abs nor its
@@ -128,11 +142,11 @@ def quant_act_1x128(x):
     m, k = x.shape
     kb = -(-k // TILE)
     xp = _pad_to(x, m, kb * TILE).reshape(m, kb, TILE)
-    q, s = _quant_groups(xp, axes=(2,))
+    q, s = _quant_groups(xp, axes=(2,), pow2=pow2)
     return q.reshape(m, kb * TILE)[:, :k].copy(), s.reshape(m, kb)
 
 
-def quant_act_128x1(x):
+def quant_act_128x1(x, pow2: bool = False):
     """128x1 tiles: the group of 128 runs along rows (tokens), one column
     (channel) wide.  x: float32 [T][C].  Returns the *transposed* results:
     codes uint8 [C][T] (token-contiguous) and scales float32 [C][ceil(T/128)],
@@ -141,12 +155,12 @@ def quant_act_128x1(x):
     t, c = x.shape
     tb = -(-t // TILE)
     xp = _pad_to(x, tb * TILE, c).reshape(tb, TILE, c)
-    q, s = _quant_groups(xp, axes=(1,))
+    q, s = _quant_groups(xp, axes=(1,), pow2=pow2)
     q = q.reshape(tb * TILE, c)[:t, :]
     return np.ascontiguousarray(q.T), np.ascontiguousarray(s.reshape(tb, c).T)
 
 
-def quant_w_128x128(w):
+def quant_w_128x128(w, pow2: bool = False):
     """128x128 blocks: per 128 output channels (rows) per 128 input channels
     (columns).  w: float32 [N][K].  Returns codes uint8 [N][K] and scales
     float32 [ceil(N/128)][ceil(K/128)]."""
@@ -154,7 +168,7 @@ def quant_w_128x128(w):
     n, k = w.shape
     nb, kb = -(-n // TILE), -(-k // TILE)
     wp = _pad_to(w, nb * TILE, kb * TILE).reshape(nb, TILE, kb, TILE)
-    q, s = _quant_groups(wp, axes=(1, 3))
+    q, s = _quant_groups(wp, axes=(1, 3), pow2=pow2)
     return q.reshape(nb * TILE, kb * TILE)[:n, :k].copy(), s.reshape(nb, kb)
 
 
