@@ -7,7 +7,7 @@ BF16): 1x128 quantization of X, 128x128 quantization of W and the block-scaled
 FP8 GEMM Y = X W^T in BF16.  Inputs are resident in HBM before the timed
 region starts.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5] [--pow2] [--no-cpu-baseline]
 
 The headline `value` is 2*M*N*K per step time (quantizers included) of the
 default workload; `kernels` lists every kernel of the step with its own
@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-variant", type=int, default=-1)
+    ap.add_argument("--pow2", action="store_true",
+                    help="power-of-two scaling factors (Section 3.3.3): the *_pow2 quantizers and the GEMM that lets "
+                         "the matrix instruction apply the scales; not the headline configuration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run three plain 256 MiB device copies and exit (scales the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
@@ -70,7 +73,7 @@ class Timed:
                     peak=self.peak, unit=self.unit, frac=achieved / self.peak)
 
 
-def build_cfg2(ds3, torch, wl, dev, variant):
+def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
     """Dense FFN up-projection Fprop.  Two input sets are rotated so that the
     quantizers stream from HBM rather than from the 256 MB last-level cache."""
     M, N, K = 4096, wl.DENSE_INTER, wl.HIDDEN
@@ -81,25 +84,27 @@ def build_cfg2(ds3, torch, wl, dev, variant):
     ws = [torch.from_numpy(w).to(dev).to(torch.bfloat16) for _ in range(nsets)]
     del x, w
     state = {"i": 0}
-    qa, sa = ds3.ds3_quant_act_1x128(xs[0])
-    qb, sb = ds3.ds3_quant_w_128x128(ws[0])
+    qa, sa = (ds3.ds3_quant_act_1x128_pow2 if pow2 else ds3.ds3_quant_act_1x128)(xs[0])
+    qb, sb = (ds3.ds3_quant_w_128x128_pow2 if pow2 else ds3.ds3_quant_w_128x128)(ws[0])
     y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     L = ds3._L()
     st = torch.cuda.current_stream().cuda_stream
+    c_quant_x = L.ds3_quant_act_1x128_pow2 if pow2 else L.ds3_quant_act_1x128
+    c_quant_w = L.ds3_quant_w_128x128_pow2 if pow2 else L.ds3_quant_w_128x128
+    c_gemm = L.ds3_gemm_fp8_bs_pow2 if pow2 else L.ds3_gemm_fp8_bs_v
 
     def quant_x():
         xi = xs[state["i"] % nsets]
-        L.ds3_quant_act_1x128(xi.data_ptr(), ds3.DS3_BF16, M, K, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0),
-                              sa.stride(1), st)
+        c_quant_x(xi.data_ptr(), ds3.DS3_BF16, M, K, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1), st)
 
     def quant_w():
         wi = ws[state["i"] % nsets]
-        L.ds3_quant_w_128x128(wi.data_ptr(), ds3.DS3_BF16, N, K, K, qb.data_ptr(), K, sb.data_ptr(), st)
+        c_quant_w(wi.data_ptr(), ds3.DS3_BF16, N, K, K, qb.data_ptr(), K, sb.data_ptr(), st)
 
     def gemm():
-        r = L.ds3_gemm_fp8_bs_v(variant, M, N, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1),
-                                qb.data_ptr(), K, sb.data_ptr(), sb.stride(0), sb.stride(1), ds3.DS3_BSCALE_128x128,
-                                y.data_ptr(), ds3.DS3_BF16, N, 0, None, 0, st)
+        r = c_gemm(variant, M, N, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1),
+                   qb.data_ptr(), K, sb.data_ptr(), sb.stride(0), sb.stride(1), ds3.DS3_BSCALE_128x128,
+                   y.data_ptr(), ds3.DS3_BF16, N, 0, None, 0, st)
         assert r == 0, r
 
     bx = M * K * (2 + 1) + M * (K // 128) * 4
@@ -118,6 +123,9 @@ def build_cfg2(ds3, torch, wl, dev, variant):
     cfg = {"workload": "cfg2: dense FFN up-projection Fprop, X[4096x7168] BF16 (1% outlier channels x50), "
                        "W[18432x7168] BF16 ~N(0,0.02); quant 1x128 + quant 128x128 + block-scaled FP8 GEMM, BF16 out",
            "M": M, "N": N, "K": K, "gemm_variant": variant}
+    if pow2:
+        cfg["workload"] += "; power-of-two scaling factors, scales applied by the matrix instruction"
+        cfg["scales"] = "pow2"
     return step, kernels, 2.0 * M * N * K, cfg, "gemm_fp8_bs"
 
 
@@ -165,9 +173,10 @@ def main():
         return
     if args.workload != "cfg2":
         from paper_2412_19437_amd import bench_extra
-        step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant)
+        step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant,
+                                                                args.pow2)
     else:
-        step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant)
+        step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant, args.pow2)
 
     for _ in range(args.warmup):
         step(False)
@@ -183,7 +192,7 @@ def main():
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tfile):
-        entry = json.load(open(tfile)).get(args.workload, {}).get(dominant)
+        entry = json.load(open(tfile)).get(args.workload + ("_pow2" if args.pow2 else ""), {}).get(dominant)
         traffic = entry["total_bytes"] if entry else None     # HBM-side bytes per launch, from profiles/
     out = {
         "metric": "block-scaled FP8 GEMM TFLOP/s + % FP8 MFMA peak; quantizer GB/s + % HBM peak",
@@ -198,7 +207,7 @@ def main():
                      "frac": dom["frac"], "traffic": traffic, "kernel": dom["name"], "avg_us": dom["avg_us"]},
         "kernels": ksum,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.pow2:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 

@@ -177,6 +177,52 @@ ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* grou
                                      void* c, ds3_dtype ct, int64_t ldc,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Power-of-two scaling factors (Section 3.3.3: the inputs of the Linear after
+ * attention and the activations quantized before MoE dispatch use factors that
+ * are integral powers of two).  The three quantizers with
+ *         s = the smallest power of two >= amax / 448     (1 if amax == 0)
+ *         r = 1 / s (exact),   q_i = E4M3_round_to_nearest_even(x_i * r)
+ * in place of the rule at the top of this file; arguments, layouts and
+ * alignment are those of the calls without the suffix.  Such a scale is an
+ * E8M0 number, so a tile can be re-tiled or re-scaled by another power of two
+ * without a second rounding of its significands.
+ */
+ds3_status ds3_quant_act_1x128_pow2(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx,
+                                    uint8_t* q, int64_t ldq,
+                                    float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+ds3_status ds3_quant_act_128x1_pow2(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx,
+                                    uint8_t* q_t, int64_t ldq,
+                                    float* s_t, int64_t s_stride_col, int64_t s_stride_tb, void* stream);
+ds3_status ds3_quant_w_128x128_pow2(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw,
+                                    uint8_t* q, int64_t ldq, float* s, void* stream);
+
+/*
+ * The two GEMMs for operands whose scales are ALL powers of two in
+ * [2^-126, 2^127] (both sa and sb; the outputs of the *_pow2 quantizers are).
+ * Same result as ds3_gemm_fp8_bs / ds3_grouped_gemm_fp8_bs on the same
+ * arguments, computed with the scales applied inside the matrix instruction
+ * (gfx950 block-scaled MFMA, E8M0 scale per 32 elements along K) and the
+ * partial sums chained in its FP32 accumulator, which removes the per-interval
+ * rescale from the vector ALU.  Only the exponent field of each scale is read:
+ * scales that are not powers of two give unspecified (finite-cost, fault-free)
+ * results.  `variant` as in the tuning hooks above, -1 = choose by shape.
+ */
+ds3_status ds3_gemm_fp8_bs_pow2(int variant, int64_t M, int64_t N, int64_t K,
+                                const uint8_t* a, int64_t lda,
+                                const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                const uint8_t* b, int64_t ldb,
+                                const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode,
+                                void* c, ds3_dtype ct, int64_t ldc, int accumulate,
+                                void* workspace, size_t workspace_bytes, void* stream);
+ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                        int64_t N, int64_t K,
+                                        const uint8_t* a, int64_t lda,
+                                        const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                        const uint8_t* b, int64_t ldb, const float* sb,
+                                        void* c, ds3_dtype ct, int64_t ldc,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of device workspace the GEMM calls need for this shape (0 today). */
 size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 

@@ -25,6 +25,8 @@ SYMBOLS = [
     "ds3_quant_act_1x128", "ds3_quant_act_128x1", "ds3_quant_w_128x128",
     "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_gemm_fp8_bs_v", "ds3_grouped_gemm_fp8_bs_v",
     "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_swiglu", "ds3_status_string",
+    "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
+    "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
 ]
 
 
@@ -41,15 +43,18 @@ def _load() -> ctypes.CDLL:
             "(there is no fallback implementation)")
     lib = ctypes.CDLL(LIB_PATH)
     i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
-    lib.ds3_quant_act_1x128.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
-    lib.ds3_quant_act_128x1.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
-    lib.ds3_quant_w_128x128.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
+    for sfx in ("", "_pow2"):
+        getattr(lib, "ds3_quant_act_1x128" + sfx).argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+        getattr(lib, "ds3_quant_act_128x1" + sfx).argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+        getattr(lib, "ds3_quant_w_128x128" + sfx).argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp]
     gemm = [i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, i64, i64, i32, vp, i32, i64, i32, vp, sz, vp]
     lib.ds3_gemm_fp8_bs.argtypes = gemm
     lib.ds3_gemm_fp8_bs_v.argtypes = [i32] + gemm
+    lib.ds3_gemm_fp8_bs_pow2.argtypes = [i32] + gemm
     grouped = [i32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i32, i64, vp, sz, vp]
     lib.ds3_grouped_gemm_fp8_bs.argtypes = grouped
     lib.ds3_grouped_gemm_fp8_bs_v.argtypes = [i32] + grouped
+    lib.ds3_grouped_gemm_fp8_bs_pow2.argtypes = [i32] + grouped
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
     lib.ds3_gemm_num_variants.argtypes = []
     lib.ds3_gemm_workspace_bytes.argtypes = [i64, i64, i64]
@@ -119,38 +124,65 @@ def _scales(rows: int, blocks: int, device, k_major: bool) -> torch.Tensor:
     return torch.empty((rows, blocks), dtype=torch.float32, device=device)
 
 
-def ds3_quant_act_1x128(x: torch.Tensor, k_major_scales: bool = True):
-    """x [M][K] FP32/BF16 -> (codes uint8 [M][K], scales FP32 logical [M][ceil(K/128)])."""
+def _quant_act_1x128(entry: str, x: torch.Tensor, k_major_scales: bool):
     m, k, ldx = _rows2d(x, "x")
     q = _codes(m, k, x.device)
     s = _scales(m, (k + 127) // 128, x.device, k_major_scales)
-    st = _L().ds3_quant_act_1x128(x.data_ptr(), _dt(x), m, k, ldx, q.data_ptr(), (k + 15) // 16 * 16,
-                                 s.data_ptr(), s.stride(0), s.stride(1), _stream())
-    _check(st, "ds3_quant_act_1x128")
+    st = getattr(_L(), entry)(x.data_ptr(), _dt(x), m, k, ldx, q.data_ptr(), (k + 15) // 16 * 16,
+                              s.data_ptr(), s.stride(0), s.stride(1), _stream())
+    _check(st, entry)
     return q, s
 
 
-def ds3_quant_act_128x1(x: torch.Tensor, k_major_scales: bool = True):
-    """x [T][C] -> (codes uint8 [C][T] token-contiguous, scales logical [C][ceil(T/128)])."""
+def _quant_act_128x1(entry: str, x: torch.Tensor, k_major_scales: bool):
     t, c, ldx = _rows2d(x, "x")
     ldq = (t + 15) // 16 * 16
     q_t = _codes(c, t, x.device)
     s_t = _scales(c, (t + 127) // 128, x.device, k_major_scales)
-    st = _L().ds3_quant_act_128x1(x.data_ptr(), _dt(x), t, c, ldx, q_t.data_ptr(), ldq,
-                                 s_t.data_ptr(), s_t.stride(0), s_t.stride(1), _stream())
-    _check(st, "ds3_quant_act_128x1")
+    st = getattr(_L(), entry)(x.data_ptr(), _dt(x), t, c, ldx, q_t.data_ptr(), ldq,
+                              s_t.data_ptr(), s_t.stride(0), s_t.stride(1), _stream())
+    _check(st, entry)
     return q_t, s_t
+
+
+def _quant_w_128x128(entry: str, w: torch.Tensor):
+    n, k, ldw = _rows2d(w, "w")
+    q = _codes(n, k, w.device)
+    s = torch.empty(((n + 127) // 128, (k + 127) // 128), dtype=torch.float32, device=w.device)
+    st = getattr(_L(), entry)(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), (k + 15) // 16 * 16, s.data_ptr(),
+                              _stream())
+    _check(st, entry)
+    return q, s
+
+
+def ds3_quant_act_1x128(x: torch.Tensor, k_major_scales: bool = True):
+    """x [M][K] FP32/BF16 -> (codes uint8 [M][K], scales FP32 logical [M][ceil(K/128)])."""
+    return _quant_act_1x128("ds3_quant_act_1x128", x, k_major_scales)
+
+
+def ds3_quant_act_1x128_pow2(x: torch.Tensor, k_major_scales: bool = True):
+    """As ds3_quant_act_1x128 with power-of-two scales."""
+    return _quant_act_1x128("ds3_quant_act_1x128_pow2", x, k_major_scales)
+
+
+def ds3_quant_act_128x1(x: torch.Tensor, k_major_scales: bool = True):
+    """x [T][C] -> (codes uint8 [C][T] token-contiguous, scales logical [C][ceil(T/128)])."""
+    return _quant_act_128x1("ds3_quant_act_128x1", x, k_major_scales)
+
+
+def ds3_quant_act_128x1_pow2(x: torch.Tensor, k_major_scales: bool = True):
+    """As ds3_quant_act_128x1 with power-of-two scales."""
+    return _quant_act_128x1("ds3_quant_act_128x1_pow2", x, k_major_scales)
 
 
 def ds3_quant_w_128x128(w: torch.Tensor):
     """w [N][K] -> (codes uint8 [N][K], scales FP32 [ceil(N/128)][ceil(K/128)])."""
-    n, k, ldw = _rows2d(w, "w")
-    q = _codes(n, k, w.device)
-    s = torch.empty(((n + 127) // 128, (k + 127) // 128), dtype=torch.float32, device=w.device)
-    st = _L().ds3_quant_w_128x128(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), (k + 15) // 16 * 16, s.data_ptr(),
-                                  _stream())
-    _check(st, "ds3_quant_w_128x128")
-    return q, s
+    return _quant_w_128x128("ds3_quant_w_128x128", w)
+
+
+def ds3_quant_w_128x128_pow2(w: torch.Tensor):
+    """As ds3_quant_w_128x128 with power-of-two scales."""
+    return _quant_w_128x128("ds3_quant_w_128x128_pow2", w)
 
 
 def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=torch.bfloat16,
@@ -158,6 +190,16 @@ def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=t
     """C[M][N] (+)= block-scaled product of codes a [M][K] (scales sa, logical
     [M][K/128]) and b [N][K] (scales sb: [ceil(N/128)][K/128], or [N][K/128]
     when sb_mode is DS3_BSCALE_PER_ROW)."""
+    return _gemm("ds3_gemm_fp8_bs_v", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant)
+
+
+def ds3_gemm_fp8_bs_pow2(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=torch.bfloat16,
+                         c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1):
+    """As ds3_gemm_fp8_bs for operands whose scales are all powers of two."""
+    return _gemm("ds3_gemm_fp8_bs_pow2", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant)
+
+
+def _gemm(entry, a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant):
     m, k, lda = _rows2d(a, "a")
     n, kb_, ldb = _rows2d(b, "b")
     if kb_ != k:
@@ -165,10 +207,10 @@ def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=t
     if c is None:
         c = _out(m, n, out_dtype, a.device)
     _, _, ldc = _rows2d(c, "c")
-    st = _L().ds3_gemm_fp8_bs_v(variant, m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1),
-                               b.data_ptr(), ldb, sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode,
-                               c.data_ptr(), _dt(c), ldc, int(accumulate), None, 0, _stream())
-    _check(st, "ds3_gemm_fp8_bs")
+    st = getattr(_L(), entry)(variant, m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1),
+                              b.data_ptr(), ldb, sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode,
+                              c.data_ptr(), _dt(c), ldc, int(accumulate), None, 0, _stream())
+    _check(st, entry)
     return c
 
 
@@ -176,6 +218,16 @@ def ds3_grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat1
                             c: torch.Tensor | None = None, variant: int = -1):
     """Per expert g: rows [off[g], off[g+1]) of a times b[g] ([G][N][K] codes,
     sb [G][ceil(N/128)][K/128]).  group_offsets: int32 device tensor of G+1."""
+    return _grouped("ds3_grouped_gemm_fp8_bs_v", a, sa, group_offsets, b, sb, out_dtype, c, variant)
+
+
+def ds3_grouped_gemm_fp8_bs_pow2(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat16,
+                                 c: torch.Tensor | None = None, variant: int = -1):
+    """As ds3_grouped_gemm_fp8_bs for operands whose scales are all powers of two."""
+    return _grouped("ds3_grouped_gemm_fp8_bs_pow2", a, sa, group_offsets, b, sb, out_dtype, c, variant)
+
+
+def _grouped(entry, a, sa, group_offsets, b, sb, out_dtype, c, variant):
     m, k, lda = _rows2d(a, "a")
     g, n, kk = b.shape
     if kk != k or not b.is_contiguous() or not sb.is_contiguous():
@@ -185,10 +237,10 @@ def ds3_grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat1
     if c is None:
         c = _out(m, n, out_dtype, a.device)
     _, _, ldc = _rows2d(c, "c")
-    st = _L().ds3_grouped_gemm_fp8_bs_v(variant, g, group_offsets.data_ptr(), m, n, k, a.data_ptr(), lda,
-                                       sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), k, sb.data_ptr(),
-                                       c.data_ptr(), _dt(c), ldc, None, 0, _stream())
-    _check(st, "ds3_grouped_gemm_fp8_bs")
+    st = getattr(_L(), entry)(variant, g, group_offsets.data_ptr(), m, n, k, a.data_ptr(), lda,
+                              sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), k, sb.data_ptr(),
+                              c.data_ptr(), _dt(c), ldc, None, 0, _stream())
+    _check(st, entry)
     return c
 
 

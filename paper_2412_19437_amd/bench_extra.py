@@ -22,8 +22,25 @@ def _quant_bytes(rows, cols, groups):
     return rows * cols * 3 + groups * 4
 
 
-def build(workload, ds3, torch, wl, dev, variant):
-    return {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](ds3, torch, wl, dev, variant)
+class _Pow2:
+    """The binding with every quantizer and GEMM replaced by its power-of-two-scale form."""
+
+    def __init__(self, ds3):
+        self._ds3 = ds3
+
+    def __getattr__(self, name):
+        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs")) and not name.endswith("_pow2"):
+            return getattr(self._ds3, name + "_pow2")
+        return getattr(self._ds3, name)
+
+
+def build(workload, ds3, torch, wl, dev, variant, pow2=False):
+    step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](
+        _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
+    if pow2:
+        cfg["workload"] += "; power-of-two scaling factors, scales applied by the matrix instruction"
+        cfg["scales"] = "pow2"
+    return step, kernels, flops, cfg, dominant
 
 
 def _bf16(torch, x, dev):

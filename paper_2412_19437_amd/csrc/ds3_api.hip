@@ -25,7 +25,7 @@ ds3_status check_quant(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, 
     return DS3_OK;
 }
 
-ds3_status gemm_common(int variant, int32_t G, const int32_t* offs, int64_t M, int64_t N, int64_t K, const uint8_t* a,
+ds3_status gemm_common(bool pow2, int variant, int32_t G, const int32_t* offs, int64_t M, int64_t N, int64_t K, const uint8_t* a,
                        int64_t lda, const float* sa, int64_t sar, int64_t sak, const uint8_t* b, int64_t ldb,
                        const float* sb, int64_t sbr, int64_t sbk, ds3_bscale mode, void* c, ds3_dtype ct, int64_t ldc,
                        int accumulate, void* stream) {
@@ -52,36 +52,75 @@ ds3_status gemm_common(int variant, int32_t G, const int32_t* offs, int64_t M, i
     p.b_group_stride = N * ldb;
     p.sb_group_stride = ((N + 127) / 128) * (K / 128);
     p.accumulate = accumulate;
-    return launch_gemm(p, ct, mode, variant, static_cast<hipStream_t>(stream));
+    return launch_gemm(p, ct, mode, variant, pow2, static_cast<hipStream_t>(stream));
+}
+
+ds3_status grouped_common(bool pow2, int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t N,
+                          int64_t K, const uint8_t* a, int64_t lda, const float* sa, int64_t sar, int64_t sak,
+                          const uint8_t* b, int64_t ldb, const float* sb, void* c, ds3_dtype ct, int64_t ldc,
+                          void* stream) {
+    if (G < 0) return DS3_ERR_SHAPE;
+    if (G == 0) return DS3_OK;
+    if (N > 0 && K > 0 && (int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
+    return gemm_common(pow2, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sar, sak, b, ldb, sb, K / 128, 1,
+                       DS3_BSCALE_128x128, c, ct, ldc, 0, stream);
 }
 
 }  // namespace
 
 extern "C" {
 
-ds3_status ds3_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
-                               int64_t ldq, float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+static ds3_status quant_1x128(int pow2, const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                              int64_t ldq, float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
     const ds3_status st = check_quant(x, xt, rows, cols, ldx, q, cols, ldq, s);
     if (st != DS3_OK || rows == 0 || cols == 0) return st;
-    return launch_quant_act_1x128(x, xt, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb,
+    return launch_quant_act_1x128(x, xt, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb, pow2,
                                   static_cast<hipStream_t>(stream));
+}
+
+static ds3_status quant_128x1(int pow2, const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx,
+                              uint8_t* q_t, int64_t ldq, float* s_t, int64_t s_stride_col, int64_t s_stride_tb,
+                              void* stream) {
+    const ds3_status st = check_quant(x, xt, rows, cols, ldx, q_t, rows, ldq, s_t);
+    if (st != DS3_OK || rows == 0 || cols == 0) return st;
+    if ((rows + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_act_128x1(x, xt, rows, cols, ldx, q_t, ldq, s_t, s_stride_col, s_stride_tb, pow2,
+                                  static_cast<hipStream_t>(stream));
+}
+
+static ds3_status quant_128x128(int pow2, const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                int64_t ldq, float* s, void* stream) {
+    const ds3_status st = check_quant(w, wt, n, k, ldw, q, k, ldq, s);
+    if (st != DS3_OK || n == 0 || k == 0) return st;
+    if ((n + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_w_128x128(w, wt, n, k, ldw, q, ldq, s, pow2, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                               int64_t ldq, float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return quant_1x128(0, x, xt, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+ds3_status ds3_quant_act_1x128_pow2(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
+                                    int64_t ldq, float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return quant_1x128(1, x, xt, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb, stream);
 }
 
 ds3_status ds3_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q_t,
                                int64_t ldq, float* s_t, int64_t s_stride_col, int64_t s_stride_tb, void* stream) {
-    const ds3_status st = check_quant(x, xt, rows, cols, ldx, q_t, rows, ldq, s_t);
-    if (st != DS3_OK || rows == 0 || cols == 0) return st;
-    if ((rows + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
-    return launch_quant_act_128x1(x, xt, rows, cols, ldx, q_t, ldq, s_t, s_stride_col, s_stride_tb,
-                                  static_cast<hipStream_t>(stream));
+    return quant_128x1(0, x, xt, rows, cols, ldx, q_t, ldq, s_t, s_stride_col, s_stride_tb, stream);
+}
+ds3_status ds3_quant_act_128x1_pow2(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q_t,
+                                    int64_t ldq, float* s_t, int64_t s_stride_col, int64_t s_stride_tb, void* stream) {
+    return quant_128x1(1, x, xt, rows, cols, ldx, q_t, ldq, s_t, s_stride_col, s_stride_tb, stream);
 }
 
 ds3_status ds3_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q, int64_t ldq,
                                float* s, void* stream) {
-    const ds3_status st = check_quant(w, wt, n, k, ldw, q, k, ldq, s);
-    if (st != DS3_OK || n == 0 || k == 0) return st;
-    if ((n + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
-    return launch_quant_w_128x128(w, wt, n, k, ldw, q, ldq, s, static_cast<hipStream_t>(stream));
+    return quant_128x128(0, w, wt, n, k, ldw, q, ldq, s, stream);
+}
+ds3_status ds3_quant_w_128x128_pow2(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                    int64_t ldq, float* s, void* stream) {
+    return quant_128x128(1, w, wt, n, k, ldw, q, ldq, s, stream);
 }
 
 ds3_status ds3_gemm_fp8_bs_v(int variant, int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda,
@@ -90,7 +129,17 @@ ds3_status ds3_gemm_fp8_bs_v(int variant, int64_t M, int64_t N, int64_t K, const
                              ds3_bscale sb_mode, void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* workspace,
                              size_t workspace_bytes, void* stream) {
     (void)workspace; (void)workspace_bytes;
-    return gemm_common(variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
+    return gemm_common(false, variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
+                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, stream);
+}
+
+ds3_status ds3_gemm_fp8_bs_pow2(int variant, int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda,
+                                const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b,
+                                int64_t ldb, const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb,
+                                ds3_bscale sb_mode, void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return gemm_common(true, variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
                        sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, stream);
 }
 
@@ -109,11 +158,18 @@ ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* grou
                                      const float* sb, void* c, ds3_dtype ct, int64_t ldc, void* workspace,
                                      size_t workspace_bytes, void* stream) {
     (void)workspace; (void)workspace_bytes;
-    if (G < 0) return DS3_ERR_SHAPE;
-    if (G == 0) return DS3_OK;
-    if (N > 0 && K > 0 && (int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
-    return gemm_common(variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
-                       sb, K / 128, 1, DS3_BSCALE_128x128, c, ct, ldc, 0, stream);
+    return grouped_common(false, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b,
+                          ldb, sb, c, ct, ldc, stream);
+}
+
+ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                        int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                                        int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
+                                        const float* sb, void* c, ds3_dtype ct, int64_t ldc, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return grouped_common(true, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b,
+                          ldb, sb, c, ct, ldc, stream);
 }
 
 ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t N, int64_t K,

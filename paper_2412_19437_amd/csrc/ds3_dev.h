@@ -48,11 +48,22 @@ __device__ __forceinline__ unsigned int row16_max_bits(unsigned int v) {
 // The two per-group factors of the quantisation contract: the stored scale
 // s = amax / 448 and the multiplier r = 448 / amax, both correctly rounded
 // FP32 divisions; an all-zero group gives s = 1, r = 0.
+//
+// With `pow2` set the scale is instead the smallest power of two not below
+// amax / 448 (the "round scaled" factors of Section 3.3.3) and r its exact
+// reciprocal.  448 = 1.75 * 2^8, so for amax = m * 2^E, 1 <= m < 2, the
+// exponent is E - 8 when m <= 1.75 and E - 7 otherwise; both factors are built
+// from exponent fields directly.
 struct GroupScale { float s, r; };
-__device__ __forceinline__ GroupScale group_scale(float amax) {
+__device__ __forceinline__ GroupScale group_scale(float amax, int pow2) {
     GroupScale g;
     if (amax == 0.0f) { g.s = 1.0f; g.r = 0.0f; }
-    else { g.s = amax / 448.0f; g.r = 448.0f / amax; }
+    else if (pow2) {
+        const unsigned int bits = as_u32(amax);
+        const unsigned int e = (bits >> 23) - 8u + ((bits & 0x7fffffu) > 0x600000u ? 1u : 0u);
+        g.s = as_f32(e << 23);
+        g.r = as_f32((254u - e) << 23);
+    } else { g.s = amax / 448.0f; g.r = 448.0f / amax; }
     return g;
 }
 

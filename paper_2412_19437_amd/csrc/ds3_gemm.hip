@@ -80,7 +80,13 @@ struct TileCtx {
     const float* sbrow_thr;   // this thread's weight-scale row (per-row mode)
 };
 
-template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
+//
+// POW2 (power-of-two scales, Section 3.3.3): the scales are E8M0 numbers, whose
+// code is the exponent field of the FP32 value, and the MFMA applies them itself
+// (one scale per lane and operand: the weight row's and the activation row's);
+// the accumulators then chain through the matrix pipe across K-steps and the
+// vector ALU does no rescaling at all.
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
     constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE, NSUB = C::NSUB;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[C::LDS_BYTES];
@@ -224,7 +230,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
             const float sav = sa_s[stage * NT + wm * C::TM + j * 16 + l16];
-            tj[j] = ROWSB ? sav : sav * sbv;
+            tj[j] = (ROWSB || POW2) ? sav : sav * sbv;
         }
     };
 
@@ -262,7 +268,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             issue_load(cur, i, NS - 1, NS - 1 < KB ? (unsigned)(NS - 1) << 7 : kOobOffset);
         float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
         float tj[FM];
-        read_tj(0, ROWSB ? 1.f : cur.sb_blk[0], tj);
+        [[maybe_unused]] float sb_c = ROWSB ? 1.f : cur.sb_blk[0];                  // block scale of THIS K-step (POW2 only)
+        read_tj(0, sb_c, tj);
         i32x8 pf[FN], qf[2];
 #pragma unroll
         for (int i = 0; i < FN; ++i) pf[i] = load_frag(smem + p_base + i * 2048);
@@ -358,6 +365,56 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
         };
 
+        // Power-of-two scales: the MFMA scales both operands itself and accumulates in
+        // place; the order of the memory operations is that of the general K-step.
+        auto kstep_p2 = [&](int kb, auto stage_tag) {
+            constexpr int S = decltype(stage_tag)::value;
+            const uint8_t* st = smem + S * STAGE;
+            constexpr int SN = (S + 1) % NS, SL = (S + NS - 1) % NS;
+            const uint8_t* nst = smem + SN * STAGE;
+            int ea[FN], eb[FM];                             // E8M0 codes = FP32 exponent fields
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+                ea[i] = (int)(as_u32(ROWSB ? sbrow_s[S * NT + wn * C::TN + i * 16 + l16] : sb_c) >> 23);
+#pragma unroll
+            for (int j = 0; j < FM; ++j) eb[j] = (int)(as_u32(tj[j]) >> 23);
+            float tjn[FM];
+            float sb_cn = sb_c;
+            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
+            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;
+            load_scales(cur, min(kb + 1, KB - 1));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < NSUB; ++s) {
+                if (s == NSUB - FN) {
+                    commit_scales(SN);
+                    barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (s < HEADN) issue_load(cur, TAILN + s, SL, koff1);
+                const int j = s / FN, i = s % FN;
+                if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(pf[i], qf[j & 1], acc[i][j], 0, 0, 0, ea[i],
+                                                                             0, eb[j]);
+                if (j == FM - 1) {
+                    pf[i] = load_frag(nst + p_base + i * 2048);
+                    if (i < TAILN) issue_load(cur, i, S, koff2);
+                    if (i == FN - 1) {
+                        qf[0] = load_frag(nst + q_base);
+                        read_tj(SN, 1.f, tjn);
+                        if constexpr (!ROWSB) {
+                            sb_cn = sb_n;
+                            sb_n = cur.sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int j = 0; j < FM; ++j) tj[j] = tjn[j];
+            sb_c = sb_cn;
+        };
+
         // The same K-step for a wave whose activation rows all lie beyond the tile's valid
         // rows (ragged expert groups, half tiles): it moves its share of the data and
         // keeps the barriers, in the same order of memory operations, but computes nothing.
@@ -397,7 +454,9 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 if (kb + 1 < KB) step(kb + 1, st1{});
             }
         };
-        if (active) kloop(kstep); else kloop(kstep_idle);
+        if (!active) kloop(kstep_idle);
+        else if constexpr (POW2) kloop(kstep_p2);
+        else kloop(kstep);
         __syncthreads();                               // every wave is done with all code stages
 
         // ---- the next tile's first K-steps fly into stages 0 .. NS-2 during this tile's epilogue ----
@@ -505,7 +564,7 @@ static int num_cus_x8() {
     return cached[dev];
 }
 
-template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED>
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
 static ds3_status launch_one(GemmParams p, hipStream_t st) {
     if (GROUPED) p.tiles_m = (p.M + C::BM - 1) / C::BM + p.G;
     else p.tiles_m = (p.M + C::BM - 1) / C::BM;
@@ -521,22 +580,33 @@ static ds3_status launch_one(GemmParams p, hipStream_t st) {
     const int64_t want = ((ntiles + 7) / 8) * 8;
     const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
     const unsigned grid = (unsigned)(want < slots ? want : slots);
-    gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
+    gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED, POW2><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
 
-template <class C>
+template <class C, bool POW2>
 static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, hipStream_t st) {
     const bool bf16 = ct == DS3_BF16;
-    if (p.G > 0) return bf16 ? launch_one<C, false, true, true>(p, st) : launch_one<C, false, false, true>(p, st);
+    if (p.G > 0)
+        return bf16 ? launch_one<C, false, true, true, POW2>(p, st) : launch_one<C, false, false, true, POW2>(p, st);
     if (mode == DS3_BSCALE_PER_ROW)
-        return bf16 ? launch_one<C, true, true, false>(p, st) : launch_one<C, true, false, false>(p, st);
-    return bf16 ? launch_one<C, false, true, false>(p, st) : launch_one<C, false, false, false>(p, st);
+        return bf16 ? launch_one<C, true, true, false, POW2>(p, st) : launch_one<C, true, false, false, POW2>(p, st);
+    return bf16 ? launch_one<C, false, true, false, POW2>(p, st) : launch_one<C, false, false, false, POW2>(p, st);
 }
 
 int gemm_num_variants() { return 3; }
 
-ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
+template <bool POW2>
+static ds3_status launch_variant(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
+    switch (variant) {
+        case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>, POW2>(p, ct, mode, st);
+        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 3>, POW2>(p, ct, mode, st);
+        case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>, POW2>(p, ct, mode, st);
+        default: return DS3_ERR_UNSUPPORTED;
+    }
+}
+
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st) {
     if (variant < 0) {
         // default choice: the 256x256 tile (also the fastest for the ragged expert groups);
         // the per-row-scale form (more live registers) takes the narrower M tile; problems with
@@ -545,12 +615,7 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
         const int64_t big = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
         if (p.G == 0 && big * 8 < 5 * (int64_t)num_cus_x8()) variant = 2;
     }
-    switch (variant) {
-        case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>>(p, ct, mode, st);
-        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 3>>(p, ct, mode, st);
-        case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>>(p, ct, mode, st);
-        default: return DS3_ERR_UNSUPPORTED;
-    }
+    return pow2 ? launch_variant<true>(p, ct, mode, variant, st) : launch_variant<false>(p, ct, mode, variant, st);
 }
 
 }  // namespace ds3

@@ -8,11 +8,11 @@
 namespace ds3 {
 
 ds3_status launch_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
-                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, hipStream_t st);
+                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, int pow2, hipStream_t st);
 ds3_status launch_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* qt,
-                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, hipStream_t st);
+                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, int pow2, hipStream_t st);
 ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
-                                  int64_t ldq, float* s, hipStream_t st);
+                                  int64_t ldq, float* s, int pow2, hipStream_t st);
 ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo,
                          hipStream_t st);
 
@@ -36,6 +36,7 @@ struct GemmParams {
 };
 
 // variant: which tile configuration to run (see ds3_gemm.hip); -1 = choose by shape.
-ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st);
+// pow2: every scale is a power of two (the matrix instruction applies them).
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st);
 
 }  // namespace ds3

@@ -60,7 +60,7 @@ template <> __device__ __forceinline__ unsigned int granule_amax_bits<F32>(const
 template <typename T, int TPG>
 __global__ __launch_bounds__(256) void quant_act_1x128_kernel(
     const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes,
-    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t ssr, int64_t ssk) {
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t ssr, int64_t ssk, int pow2) {
     constexpr int EPL = T::EPL;
     constexpr int GPT = 8 / EPL;                  // granules per lane per tile (16 lanes x 8 elements)
     constexpr int ESZ = 16 / EPL;                 // bytes per element
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void quant_act_1x128_kernel(
 #pragma unroll
         for (int h = 0; h < GPT; ++h) m = umax(m, granule_amax_bits<T>(g[t][h]));
         m = row16_max_bits(m);
-        const GroupScale gs = group_scale(as_f32(m));
+        const GroupScale gs = group_scale(as_f32(m), pow2);
         if (lane16 == 0) s[row * ssr + (kb0 + t) * ssk] = gs.s;
 #pragma unroll
         for (int h = 0; h < GPT; ++h) {
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void quant_act_1x128_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void quant_w_128x128_kernel(
     const uint8_t* __restrict__ w, int64_t n, int64_t k, int64_t ldw_bytes,
-    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t nkb) {
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t nkb, int pow2) {
     constexpr int EPL = T::EPL;
     constexpr int ESZ = 16 / EPL;
     constexpr int LPR = 128 / EPL;                // lanes per block row
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void quant_w_128x128_kernel(
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 16; ++i) m = umax(m, red[i]);
-    const GroupScale gs = group_scale(as_f32(m));
+    const GroupScale gs = group_scale(as_f32(m), pow2);
     if (threadIdx.x == 0) s[nb * nkb + kb] = gs.s;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void quant_w_128x128_kernel(
 template <typename T>
 __global__ __launch_bounds__(256, (T::EPL == 8 ? 7 : 4)) void quant_act_128x1_kernel(
     const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes,
-    uint8_t* __restrict__ qt, int64_t ldq, float* __restrict__ st, int64_t ssc, int64_t sst) {
+    uint8_t* __restrict__ qt, int64_t ldq, float* __restrict__ st, int64_t ssc, int64_t sst, int pow2) {
     constexpr int EPL = T::EPL;
     constexpr int ESZ = 16 / EPL;
     constexpr int LPR = 128 / EPL;                // lanes across the 128 channels
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256, (T::EPL == 8 ? 7 : 4)) void quant_act_128x1_ke
         unsigned int m = 0;
 #pragma unroll
         for (int j = 0; j < NSL; ++j) m = umax(m, part[j][threadIdx.x]);
-        const GroupScale gs = group_scale(as_f32(m));
+        const GroupScale gs = group_scale(as_f32(m), pow2);
         rmul[threadIdx.x] = gs.r;
         if (c0 + threadIdx.x < cols) st[(c0 + threadIdx.x) * ssc + (int64_t)blockIdx.y * sst] = gs.s;
     }
@@ -298,10 +298,10 @@ static ds3_status launch_status() { return hipGetLastError() == hipSuccess ? DS3
 
 template <typename T, int TPG>
 static void launch_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx_bytes, uint8_t* q, int64_t ldq, float* s,
-                         int64_t ssr, int64_t ssk, hipStream_t st) {
+                         int64_t ssr, int64_t ssk, int pow2, hipStream_t st) {
     const int64_t nkb = (cols + 127) / 128;
     dim3 grid((unsigned)((rows + 15) / 16), (unsigned)((nkb + TPG - 1) / TPG));
-    quant_act_1x128_kernel<T, TPG><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx_bytes, q, ldq, s, ssr, ssk);
+    quant_act_1x128_kernel<T, TPG><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx_bytes, q, ldq, s, ssr, ssk, pow2);
 }
 
 // Tiles per 16-lane row group: the value in 4..9 whose grid fills whole residency waves
@@ -323,12 +323,12 @@ static int pick_tiles_per_group(int64_t rows, int64_t nkb) {
 }
 
 ds3_status launch_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q,
-                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, hipStream_t st) {
+                                  int64_t ldq, float* s, int64_t ssr, int64_t ssk, int pow2, hipStream_t st) {
     const int tpg = pick_tiles_per_group(rows, (cols + 127) / 128);
 #define DS3_CASE(N)                                                                                      \
     case N:                                                                                              \
-        if (xt == DS3_BF16) launch_1x128<Bf16, N>(x, rows, cols, ldx * 2, q, ldq, s, ssr, ssk, st);      \
-        else launch_1x128<F32, N>(x, rows, cols, ldx * 4, q, ldq, s, ssr, ssk, st);                      \
+        if (xt == DS3_BF16) launch_1x128<Bf16, N>(x, rows, cols, ldx * 2, q, ldq, s, ssr, ssk, pow2, st); \
+        else launch_1x128<F32, N>(x, rows, cols, ldx * 4, q, ldq, s, ssr, ssk, pow2, st);                \
         break;
     switch (tpg) {
         DS3_CASE(4) DS3_CASE(5) DS3_CASE(6) DS3_CASE(7) DS3_CASE(8) DS3_CASE(9)
@@ -339,23 +339,23 @@ ds3_status launch_quant_act_1x128(const void* x, ds3_dtype xt, int64_t rows, int
 }
 
 ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
-                                  int64_t ldq, float* s, hipStream_t st) {
+                                  int64_t ldq, float* s, int pow2, hipStream_t st) {
     const int64_t nkb = (k + 127) / 128, nnb = (n + 127) / 128;
     dim3 grid((unsigned)nkb, (unsigned)nnb);
     if (wt == DS3_BF16)
-        quant_w_128x128_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 2, q, ldq, s, nkb);
+        quant_w_128x128_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 2, q, ldq, s, nkb, pow2);
     else
-        quant_w_128x128_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 4, q, ldq, s, nkb);
+        quant_w_128x128_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 4, q, ldq, s, nkb, pow2);
     return launch_status();
 }
 
 ds3_status launch_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, uint8_t* qt,
-                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, hipStream_t st) {
+                                  int64_t ldq, float* s_t, int64_t ssc, int64_t sst, int pow2, hipStream_t st) {
     dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
     if (xt == DS3_BF16)
-        quant_act_128x1_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 2, qt, ldq, s_t, ssc, sst);
+        quant_act_128x1_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 2, qt, ldq, s_t, ssc, sst, pow2);
     else
-        quant_act_128x1_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 4, qt, ldq, s_t, ssc, sst);
+        quant_act_128x1_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 4, qt, ldq, s_t, ssc, sst, pow2);
     return launch_status();
 }
 
