@@ -32,8 +32,13 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--settle-ms", type=float, default=250.0,
+                    help="before the warmup steps, run untimed steps for this long so that the GPU has left its "
+                         "idle power state and its clocks have settled (the first ~15 ms after idle run 15-20%% slower)")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="bracket the kernels with HIP events on every n-th timed step only (1 = every step)")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-variant", type=int, default=-1)
@@ -178,12 +183,18 @@ def main():
     else:
         step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant, args.pow2)
 
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(8):
+            step(False)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
+    every = max(1, min(args.event_every, args.steps // 8 if args.steps >= 16 else 1))
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(True)
+    for i in range(args.steps):
+        step(i % every == 0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -198,7 +209,8 @@ def main():
         "metric": "block-scaled FP8 GEMM TFLOP/s + % FP8 MFMA peak; quantizer GB/s + % HBM peak",
         "value": flops * args.steps / dt / 1e12,
         "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
+        "event_timed_steps": len(kernels[0].pairs),
         "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
