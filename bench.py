@@ -41,6 +41,7 @@ def parse():
                     help="bracket the kernels with HIP events on every n-th timed step only (1 = every step)")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the two machine probes (sustained MFMA rate, L2->LDS feed)")
     ap.add_argument("--gemm-variant", type=int, default=-1)
     ap.add_argument("--pow2", action="store_true",
                     help="power-of-two scaling factors (Section 3.3.3): the *_pow2 quantizers and the GEMM that lets "
@@ -134,6 +135,35 @@ def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
     return step, kernels, 2.0 * M * N * K, cfg, "gemm_fp8_bs"
 
 
+def machine_probes(ds3, torch, dev):
+    """What this chip sustains: FP8 MFMA rate from registers, and L2 -> LDS feed rate per compute unit."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    out_f = torch.empty(cus * 8, dtype=torch.float32, device=dev)
+    out_i = torch.empty(cus, dtype=torch.int32, device=dev)
+    src = torch.zeros(64 << 20, dtype=torch.uint8, device=dev)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e30
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3)
+        return best
+
+    iters = 4000
+    t = timed(lambda: ds3.ds3_probe_mfma_fp8(iters, cus, out_f))
+    mfma = cus * 8 * iters * 32 * 65536.0 / t / 1e12
+    t = timed(lambda: ds3.ds3_probe_lds_feed(src, 7168, iters, cus, out_i))
+    feed = iters * 65536.0 / t / 1e9
+    return {"mfma_fp8_register_loop_tflops": mfma, "mfma_fp8_register_loop_frac_of_peak": mfma / PEAK_FP8_TFLOPS,
+            "l2_to_lds_feed_gbs_per_cu": feed, "l2_to_lds_feed_tbs_total": feed * cus / 1e3,
+            "feed_needed_gbs_per_cu_at_register_loop_rate": 65536.0 / (2.0 * 256 * 256 * 128 / (mfma * 1e12 / cus)) / 1e9,
+            "note": "a 256x256 FP8 tile consumes 64 KiB of operands per 128-deep K-step (2*256*256*128 flop)"}
+
+
 def cpu_baseline(wl):
     """The oracle as it stands on a bounded sample of the same workload."""
     import numpy as np
@@ -219,6 +249,8 @@ def main():
                      "frac": dom["frac"], "traffic": traffic, "kernel": dom["name"], "avg_us": dom["avg_us"]},
         "kernels": ksum,
     }
+    if not args.no_probes:
+        out["machine"] = machine_probes(ds3, torch, dev)
     if not args.no_cpu_baseline and not args.pow2:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

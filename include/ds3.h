@@ -237,6 +237,24 @@ size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
                       void* out, int64_t ldo, void* stream);
 
+/*
+ * Machine probes for the benchmark (they compute nothing of the method; they
+ * exist so that a roofline fraction can be read against what this chip
+ * sustains, not only against the published peak).
+ *
+ * ds3_probe_mfma_fp8: `workgroups` workgroups of 8 waves, each wave issuing
+ * iters * 32 FP8 16x16x128 MFMAs (65536 flop each) on register operands.
+ * out: DEVICE, workgroups * 8 floats (checksums, ignored).
+ *
+ * ds3_probe_lds_feed: every workgroup moves iters * 64 KiB from `src` (DEVICE,
+ * window_bytes < 2^31, rows of 128 bytes taken at `row_stride` bytes, a
+ * multiple of 128, window_bytes >= 4096 * row_stride) into LDS with the
+ * GEMM's load pattern.  out: DEVICE, `workgroups` words.
+ */
+ds3_status ds3_probe_mfma_fp8(int iters, int workgroups, float* out, void* stream);
+ds3_status ds3_probe_lds_feed(const void* src, size_t window_bytes, int64_t row_stride, int iters, int workgroups,
+                              uint32_t* out, void* stream);
+
 /* Static, never NULL. */
 const char* ds3_status_string(ds3_status st);
 

@@ -27,6 +27,7 @@ SYMBOLS = [
     "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_swiglu", "ds3_status_string",
     "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
+    "ds3_probe_mfma_fp8", "ds3_probe_lds_feed",
 ]
 
 
@@ -56,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.ds3_grouped_gemm_fp8_bs_v.argtypes = [i32] + grouped
     lib.ds3_grouped_gemm_fp8_bs_pow2.argtypes = [i32] + grouped
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
+    lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
+    lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
     lib.ds3_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.ds3_gemm_workspace_bytes.restype = sz
@@ -261,3 +264,18 @@ def ds3_gemm_num_variants() -> int:
 
 def ds3_gemm_workspace_bytes(m: int, n: int, k: int) -> int:
     return int(_L().ds3_gemm_workspace_bytes(m, n, k))
+
+
+def ds3_probe_mfma_fp8(iters: int, workgroups: int, out: torch.Tensor):
+    """Enqueue the register-only FP8 MFMA loop (workgroups * 8 waves * iters * 32 MFMAs of 65536 flop)."""
+    if out.dtype != torch.float32 or out.numel() < workgroups * 8:
+        raise ValueError("out must hold workgroups * 8 floats")
+    _check(_L().ds3_probe_mfma_fp8(iters, workgroups, out.data_ptr(), _stream()), "ds3_probe_mfma_fp8")
+
+
+def ds3_probe_lds_feed(src: torch.Tensor, row_stride: int, iters: int, workgroups: int, out: torch.Tensor):
+    """Enqueue the L2 -> LDS streaming loop (each workgroup moves iters * 64 KiB)."""
+    if src.dtype != torch.uint8 or not src.is_contiguous() or out.dtype != torch.int32 or out.numel() < workgroups:
+        raise ValueError("src: contiguous uint8; out: int32 of at least `workgroups` elements")
+    _check(_L().ds3_probe_lds_feed(src.data_ptr(), src.numel(), row_stride, iters, workgroups, out.data_ptr(), _stream()),
+           "ds3_probe_lds_feed")

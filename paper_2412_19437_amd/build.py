@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libds3.so")
-SOURCES = ["ds3_api.hip", "ds3_quant.hip", "ds3_gemm.hip"]
+SOURCES = ["ds3_api.hip", "ds3_quant.hip", "ds3_gemm.hip", "ds3_probe.hip"]
 
 # -ffp-contract=off: the quantizers' FP32 operation sequence is a bit-exact
 #   contract; FMAs in the GEMM are written explicitly.

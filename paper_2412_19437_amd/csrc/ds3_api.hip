@@ -197,6 +197,27 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, v
     return launch_swiglu(h, rows, inter, ldh, out, ldo, static_cast<hipStream_t>(stream));
 }
 
+ds3_status ds3_probe_mfma_fp8(int iters, int workgroups, float* out, void* stream) {
+    if (iters < 0 || workgroups < 0) return DS3_ERR_SHAPE;
+    if (iters == 0 || workgroups == 0) return DS3_OK;
+    if (!out) return DS3_ERR_NULL;
+    if (iters > (1 << 24) || workgroups > (1 << 20)) return DS3_ERR_UNSUPPORTED;
+    return launch_probe_mfma(iters, out, workgroups, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_probe_lds_feed(const void* src, size_t window_bytes, int64_t row_stride, int iters, int workgroups,
+                              uint32_t* out, void* stream) {
+    if (iters < 0 || workgroups < 0 || row_stride < 128 || row_stride % 128) return DS3_ERR_SHAPE;
+    if (iters == 0 || workgroups == 0) return DS3_OK;
+    if (!src || !out) return DS3_ERR_NULL;
+    if (!aligned16(src)) return DS3_ERR_ALIGN;
+    // the kernel addresses 8 panels of 512 rows with 32-bit offsets below the out-of-range marker
+    if (window_bytes >= (1ull << 31) || (uint64_t)row_stride * 4096 > window_bytes) return DS3_ERR_UNSUPPORTED;
+    if (iters > (1 << 24) || workgroups > (1 << 20)) return DS3_ERR_UNSUPPORTED;
+    return launch_probe_feed(src, (unsigned)window_bytes, (int)row_stride, iters, out, workgroups,
+                             static_cast<hipStream_t>(stream));
+}
+
 const char* ds3_status_string(ds3_status st) {
     switch (st) {
         case DS3_OK: return "ok";

@@ -16,6 +16,10 @@ ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_
 ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo,
                          hipStream_t st);
 
+ds3_status launch_probe_mfma(int iters, float* out, int blocks, hipStream_t st);
+ds3_status launch_probe_feed(const void* src, unsigned window, int row_stride, int iters, unsigned* out, int blocks,
+                             hipStream_t st);
+
 // One description for the dense and the grouped GEMM.  Dense: G == 0.
 struct GemmParams {
     const uint8_t* a;      // [M][lda] activation-side codes
