@@ -238,6 +238,25 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
                       void* out, int64_t ldo, void* stream);
 
 /*
+ * SwiGLU fused with the 1x128 quantization of its output (Section 3.3.3,
+ * Low-Precision Activation: the down projection takes the SwiGLU output
+ * quantized to FP8; Section 3.5.2 asks for the cast to be fused with the
+ * producer so that the activation is not written to and re-read from HBM).
+ * Same result, bit for bit, as ds3_swiglu followed by ds3_quant_act_1x128
+ * (or its _pow2 form) on the BF16 activation: the activation is rounded to
+ * BF16 in registers before its max-abs is taken.
+ *   h  as in ds3_swiglu;  q [rows][ldq] codes with `inter` valid columns;
+ *   s  as in ds3_quant_act_1x128 with cols = inter.
+ * inter % 8 == 0, h and q 16-byte aligned, ldh % 8 == 0, ldq % 16 == 0.
+ */
+ds3_status ds3_swiglu_quant_1x128(const void* h, int64_t rows, int64_t inter, int64_t ldh,
+                                  uint8_t* q, int64_t ldq,
+                                  float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inter, int64_t ldh,
+                                       uint8_t* q, int64_t ldq,
+                                       float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+
+/*
  * Machine probes for the benchmark (they compute nothing of the method; they
  * exist so that a roofline fraction can be read against what this chip
  * sustains, not only against the published peak).

@@ -233,3 +233,19 @@ def swiglu(h) -> np.ndarray:
     inter = h.shape[1] // 2
     g, u = h[:, :inter], h[:, inter:]
     return g / (1.0 + np.exp(-g)) * u
+
+
+def round_to_bf16(x) -> np.ndarray:
+    """Round to the nearest BF16 value, ties to even; returned as float32.  The
+    input is first brought to float32 (the producers compute in FP32)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(x))
+
+
+def swiglu_quant_1x128(h, pow2: bool = False):
+    """The SwiGLU output as the down projection receives it (Section 3.3.3,
+    Low-Precision Activation): the activation is a BF16 tensor (reading: rounded
+    from the FP32 evaluation), quantized per 1x128 tile.  Defined as the
+    composition of the two steps, which is what a fused kernel must equal."""
+    return quant_act_1x128(round_to_bf16(swiglu(h)), pow2=pow2)

@@ -27,7 +27,7 @@ SYMBOLS = [
     "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_swiglu", "ds3_status_string",
     "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
-    "ds3_probe_mfma_fp8", "ds3_probe_lds_feed",
+    "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
 ]
 
 
@@ -57,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.ds3_grouped_gemm_fp8_bs_v.argtypes = [i32] + grouped
     lib.ds3_grouped_gemm_fp8_bs_pow2.argtypes = [i32] + grouped
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
+    lib.ds3_swiglu_quant_1x128.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_swiglu_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
@@ -256,6 +258,29 @@ def ds3_swiglu(h: torch.Tensor):
     st = _L().ds3_swiglu(h.data_ptr(), rows, two_i // 2, ldh, out.data_ptr(), two_i // 2, _stream())
     _check(st, "ds3_swiglu")
     return out
+
+
+def _swiglu_quant(entry: str, h: torch.Tensor, k_major_scales: bool):
+    rows, two_i, ldh = _rows2d(h, "h")
+    if h.dtype != torch.bfloat16 or two_i % 2:
+        raise TypeError("h must be BF16 with an even number of columns")
+    inter = two_i // 2
+    q = _codes(rows, inter, h.device)
+    s = _scales(rows, (inter + 127) // 128, h.device, k_major_scales)
+    st = getattr(_L(), entry)(h.data_ptr(), rows, inter, ldh, q.data_ptr(), (inter + 15) // 16 * 16,
+                              s.data_ptr(), s.stride(0), s.stride(1), _stream())
+    _check(st, entry)
+    return q, s
+
+
+def ds3_swiglu_quant_1x128(h: torch.Tensor, k_major_scales: bool = True):
+    """h [rows][2*inter] BF16 (gate | up) -> 1x128-quantized silu(gate) * up: (codes [rows][inter], scales)."""
+    return _swiglu_quant("ds3_swiglu_quant_1x128", h, k_major_scales)
+
+
+def ds3_swiglu_quant_1x128_pow2(h: torch.Tensor, k_major_scales: bool = True):
+    """As ds3_swiglu_quant_1x128 with power-of-two scales."""
+    return _swiglu_quant("ds3_swiglu_quant_1x128_pow2", h, k_major_scales)
 
 
 def ds3_gemm_num_variants() -> int:

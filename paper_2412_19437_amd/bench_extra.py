@@ -22,6 +22,9 @@ def _quant_bytes(rows, cols, groups):
     return rows * cols * 3 + groups * 4
 
 
+_UNFUSED_SWIGLU = False
+
+
 class _Pow2:
     """The binding with every quantizer and GEMM replaced by its power-of-two-scale form."""
 
@@ -29,12 +32,15 @@ class _Pow2:
         self._ds3 = ds3
 
     def __getattr__(self, name):
-        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs")) and not name.endswith("_pow2"):
+        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_swiglu_quant")) \
+                and not name.endswith("_pow2"):
             return getattr(self._ds3, name + "_pow2")
         return getattr(self._ds3, name)
 
 
-def build(workload, ds3, torch, wl, dev, variant, pow2=False):
+def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False):
+    global _UNFUSED_SWIGLU
+    _UNFUSED_SWIGLU = unfused_swiglu
     step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](
         _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
     if pow2:
@@ -81,6 +87,9 @@ def _cfg3(ds3, torch, wl, dev, variant):
     def quant_h():
         st["qh"], st["sh"] = ds3.ds3_quant_act_1x128(st["act"])
 
+    def swiglu_quant():
+        st["qh"], st["sh"] = ds3.ds3_swiglu_quant_1x128(st["h"])
+
     def gemm2():
         st["y"] = ds3.ds3_grouped_gemm_fp8_bs(st["qh"], st["sh"], offd, q2v, s2v, variant=variant)
 
@@ -94,6 +103,11 @@ def _cfg3(ds3, torch, wl, dev, variant):
         Timed("quant_act_1x128(h)", quant_h, "GB/s", _quant_bytes(rows, I, rows * I // 128) / 1e9, "hbm", PEAK_HBM_GBS),
         Timed("grouped_gemm_fp8_bs(down)", gemm2, "TFLOP/s", f2 / 1e12, "mfma", PEAK_FP8_TFLOPS),
     ]
+    if not _UNFUSED_SWIGLU:
+        # one pass: reads the gate|up output (4 B per activation), writes codes + scales (1.03 B)
+        fused = Timed("swiglu_quant_1x128(fused)", swiglu_quant, "GB/s", (rows * I * 5 + rows * I // 128 * 4) / 1e9, "hbm",
+                      PEAK_HBM_GBS)
+        kernels = kernels[:3] + [fused] + kernels[5:]
 
     def step(record):
         for k in kernels:
@@ -101,6 +115,7 @@ def _cfg3(ds3, torch, wl, dev, variant):
 
     cfg = {"workload": "cfg3: MoE grouped Fprop, 32 local experts of 256, 8192 tokens top-8 (sigmoid affinity + bias), "
                        "gate|up [n_e x 7168]x[4096x7168]^T, SwiGLU, down [n_e x 2048]x[7168x2048]^T, BF16 out",
+           "swiglu": "separate SwiGLU and quantizer kernels" if _UNFUSED_SWIGLU else "fused with the 1x128 quantizer",
            "rows": rows, "group_sizes_min_med_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
            "gemm_variant": variant}
     return step, kernels, f1 + f2, cfg, "grouped_gemm_fp8_bs(gate|up)"

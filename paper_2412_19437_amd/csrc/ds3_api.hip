@@ -197,6 +197,26 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, v
     return launch_swiglu(h, rows, inter, ldh, out, ldo, static_cast<hipStream_t>(stream));
 }
 
+static ds3_status swiglu_quant(int pow2, const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
+                               float* s, int64_t ssr, int64_t ssk, void* stream) {
+    if (rows < 0 || inter < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || inter == 0) return DS3_OK;
+    if (!h || !q || !s) return DS3_ERR_NULL;
+    if (ldh < 2 * inter || ldq < inter) return DS3_ERR_SHAPE;
+    if (!aligned16(h) || !aligned16(q) || inter % 8 || ldh % 8 || ldq % 16) return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || inter > kMaxDim) return DS3_ERR_UNSUPPORTED;
+    return launch_swiglu_quant_1x128(h, rows, inter, ldh, q, ldq, s, ssr, ssk, pow2, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_swiglu_quant_1x128(const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
+                                  float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return swiglu_quant(0, h, rows, inter, ldh, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
+                                       float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return swiglu_quant(1, h, rows, inter, ldh, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+
 ds3_status ds3_probe_mfma_fp8(int iters, int workgroups, float* out, void* stream) {
     if (iters < 0 || workgroups < 0) return DS3_ERR_SHAPE;
     if (iters == 0 || workgroups == 0) return DS3_OK;

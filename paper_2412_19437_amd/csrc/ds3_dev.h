@@ -67,6 +67,13 @@ __device__ __forceinline__ GroupScale group_scale(float amax, int pow2) {
     return g;
 }
 
+// silu(g) * u in FP32 with the hardware reciprocal (1 ulp) instead of an IEEE
+// division: the result is rounded to BF16 (8 significant bits) by every caller,
+// and all callers share this one expression so that they agree bit for bit.
+__device__ __forceinline__ float silu_mul(float g, float u) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
+
 // Four FP32 values -> four E4M3 codes in one 32-bit word (lowest address in
 // the low byte); the hardware conversion rounds to nearest even.
 __device__ __forceinline__ unsigned int cvt4_e4m3(float a, float b, float c, float d) {

@@ -288,9 +288,62 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const uint8_t* __restrict__
     widen<Bf16>(gg, g);
     widen<Bf16>(uu, u);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = g[i] / (1.0f + __expf(-g[i])) * u[i];
+    for (int i = 0; i < 8; ++i) o[i] = silu_mul(g[i], u[i]);
     u32x4 w = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
     st_stream(out + row * ldo_bytes + gi * 16, w);
+}
+
+// =============================================================================
+// SwiGLU fused with the 1x128 quantizer of the down projection's input: the
+// activation is rounded to BF16 exactly as swiglu_kernel writes it, but goes
+// straight from registers into the max-abs / scale / cast steps of the 1x128
+// quantizer, so the BF16 tensor never travels to HBM and back.
+// =============================================================================
+template <int TPG>
+__global__ __launch_bounds__(256) void swiglu_quant_1x128_kernel(
+    const uint8_t* __restrict__ h, int64_t rows, int64_t inter, int64_t ldh_bytes,
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t ssr, int64_t ssk, int pow2) {
+    const int lane16 = threadIdx.x & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (row >= rows) return;                      // a whole DPP row leaves together
+    const int64_t kb0 = (int64_t)blockIdx.y * TPG;
+    const int64_t nkb = (inter + 127) >> 7;
+    const uint8_t* hr = h + row * ldh_bytes;
+    u32x4 gg[TPG], uu[TPG];
+    bool ok[TPG];
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+        const int64_t col = (kb0 + t) * 128 + lane16 * 8;
+        ok[t] = col < inter;
+        gg[t] = u32x4{0u, 0u, 0u, 0u};
+        uu[t] = u32x4{0u, 0u, 0u, 0u};
+        if (ok[t]) {
+            gg[t] = ld_stream(hr + col * 2);
+            uu[t] = ld_stream(hr + (inter + col) * 2);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+        if (kb0 + t >= nkb) break;
+        float g[8], u[8], o[8];
+        widen<Bf16>(gg[t], g);
+        widen<Bf16>(uu[t], u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = silu_mul(g[i], u[i]);
+        const u32x4 w = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7])};
+        const unsigned int m = row16_max_bits(granule_amax_bits<Bf16>(w));
+        const GroupScale gs = group_scale(as_f32(m), pow2);
+        if (lane16 == 0) s[row * ssr + (kb0 + t) * ssk] = gs.s;
+        float v[8];
+        widen<Bf16>(w, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] * gs.r;
+        if (ok[t]) {
+            const int64_t col = (kb0 + t) * 128 + lane16 * 8;
+            u32x2 c = {cvt4_e4m3(v[0], v[1], v[2], v[3]), cvt4_e4m3(v[4], v[5], v[6], v[7])};
+            st_stream(q + row * ldq + col, c);
+        }
+    }
 }
 
 // ----- host launchers -----------------------------------------------------------
@@ -364,6 +417,15 @@ ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh
     const int64_t n = rows * (inter / 8);
     swiglu_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>((const uint8_t*)h, rows, inter, ldh * 2,
                                                                      (uint8_t*)out, ldo * 2);
+    return launch_status();
+}
+
+ds3_status launch_swiglu_quant_1x128(const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
+                                     float* s, int64_t ssr, int64_t ssk, int pow2, hipStream_t st) {
+    constexpr int TPG = 4;
+    const int64_t nkb = (inter + 127) / 128;
+    dim3 grid((unsigned)((rows + 15) / 16), (unsigned)((nkb + TPG - 1) / TPG));
+    swiglu_quant_1x128_kernel<TPG><<<grid, 256, 0, st>>>((const uint8_t*)h, rows, inter, ldh * 2, q, ldq, s, ssr, ssk, pow2);
     return launch_status();
 }
 

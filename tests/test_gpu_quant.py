@@ -157,3 +157,24 @@ def test_swiglu(ds3):
     ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -120))) - 7)
     assert np.all(np.abs(out - ref) <= ulp)
     assert np.mean(np.abs(out - ref) <= 0.5 * ulp * 1.001) > 0.99
+
+
+@pytest.mark.parametrize("pow2", [False, True])
+@pytest.mark.parametrize("shape", [(300, 512), (64, 4096), (17, 400), (1, 16)])
+def test_swiglu_fused_with_quantizer(ds3, shape, pow2):
+    """The fused kernel must equal, bit for bit, the 1x128 quantization of the BF16
+    activation that ds3_swiglu writes (itself checked against the oracle above); the
+    oracle decides the codes from those same BF16 values.  Against the all-oracle
+    composition (FP64 exponential) a BF16 ulp of difference in the activation can move
+    a code, so there the agreement is statistical."""
+    announce(f"swiglu+quant {shape} pow2={pow2}")
+    h = wl.normal(shape, 2.0, 6)
+    hd = dev(h, bf16=True)
+    fused = (ds3.ds3_swiglu_quant_1x128_pow2 if pow2 else ds3.ds3_swiglu_quant_1x128)(hd)
+    act = host(ds3.ds3_swiglu(hd))
+    _cmp_codes_scales(*fused, *orc.quant_act_1x128(act, pow2=pow2), "fused vs quant(swiglu)")
+    q_ref, s_ref = orc.swiglu_quant_1x128(h, pow2=pow2)
+    q, s = host(fused[0]), host(fused[1])
+    assert np.mean(q == q_ref) > 0.98 and np.mean(s == s_ref) > 0.9
+    deq, deq_ref = orc.dequant_rows(q, s), orc.dequant_rows(q_ref, s_ref)
+    assert np.linalg.norm(deq - deq_ref) <= 2e-2 * np.linalg.norm(deq_ref)

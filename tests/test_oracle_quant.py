@@ -193,3 +193,38 @@ def test_fine_grained_beats_per_tensor_on_outliers():
     r = np.float32(448) / np.abs(x).max()
     coarse = orc.e4m3_decode(orc.e4m3_encode_rne_sat((x * r).astype(np.float32))) / r - x
     assert np.linalg.norm(fine) < 0.8 * np.linalg.norm(coarse)
+
+
+def test_round_to_bf16_against_library_cast_and_ties():
+    import torch
+    rng = np.random.default_rng(81)
+    x = np.concatenate([rng.standard_normal(20000) * np.exp(rng.standard_normal(20000) * 8),
+                        [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 0.0, -0.0, 2.0 ** -120]]).astype(np.float32)
+    got = orc.round_to_bf16(x)
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(got.view(np.uint32), lib.view(np.uint32))
+    assert got[-6] == 1.0 and got[-5] == np.float32(1.0 + 2.0 ** -6)     # ties go to the even significand
+    assert np.array_equal(got, wl.bf16_round(x))                          # the generators' own rounding agrees
+
+
+def test_swiglu_quant_is_the_composition_and_closed_forms():
+    h = wl.normal((5, 512), 2.0, 82)
+    q, s = orc.swiglu_quant_1x128(h)
+    act = orc.swiglu(h)
+    # every dequantised value is within BF16 rounding plus half an E4M3 step of the FP64 activation
+    deq = orc.dequant_rows(q, s)
+    amax = np.abs(act.reshape(5, 2, 128)).max(axis=2)
+    step = np.repeat(amax / 448 * 2.0 ** 4, 128, axis=1)                  # coarsest E4M3 step, times the scale
+    assert np.all(np.abs(deq - act) <= step + np.abs(act) * 2.0 ** -8)
+    # gate == 0 gives an all-zero tile: scale 1, zero codes
+    h0 = h.copy(); h0[:, :256] = 0
+    q0, s0 = orc.swiglu_quant_1x128(h0)
+    assert np.all(s0 == 1.0) and np.all((q0 & 0x7F) == 0)
+    # a large positive gate passes `up` through: silu(g) -> g
+    h1 = np.zeros((1, 256), np.float32); h1[0, :128] = 64.0; h1[0, 128:] = np.linspace(-1, 1, 128, dtype=np.float32)
+    q1, s1 = orc.swiglu_quant_1x128(h1)
+    q1r, s1r = orc.quant_act_1x128(orc.round_to_bf16(64.0 * h1[:, 128:].astype(np.float64)))
+    assert np.array_equal(q1, q1r) and np.array_equal(s1, s1r)
+    # power-of-two form: same activation, scales rounded up
+    q2, s2 = orc.swiglu_quant_1x128(h, pow2=True)
+    assert np.all(s2 >= s) and np.all(s2 < 2 * s.astype(np.float64))
