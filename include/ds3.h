@@ -238,6 +238,31 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
                       void* out, int64_t ldo, void* stream);
 
 /*
+ * Re-tiling of a cached FP8 activation for the weight-gradient GEMM (Section
+ * 3.5.2, Support for Transposed GEMM Operations: the activation kept from the
+ * forward pass in 1x128 tiles is read back, dequantized, transposed and
+ * re-quantized into 128x1 tiles; Section 3.3.3 (1)).  Per element
+ *     v = fl32(dec(q[t][c]) * s(t, c / 128))
+ * and then exactly ds3_quant_act_128x1 (or its _pow2 form) applied to v:
+ *   q    [rows][ldq]  codes of the 1x128-quantized matrix, rows = tokens
+ *   s    scale of (token t, block kb) at s[t * s_stride_row + kb * s_stride_kb]
+ *   q_t  [cols][ldqt] code of (token t, channel c) at q_t[c * ldqt + t]
+ *   s_t  scale of (channel c, token block tb) at s_t[c * st_stride_col + tb * st_stride_tb]
+ * One byte read and one written per element (the BF16 source costs two to read).
+ * With power-of-two scales on both sides the significands are not rounded a
+ * second time unless a value falls below the new tile's normal range.
+ * cols % 16 == 0, ldq % 16 == 0, ldqt % 16 == 0, q and q_t 16-byte aligned.
+ */
+ds3_status ds3_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq,
+                                     const float* s, int64_t s_stride_row, int64_t s_stride_kb,
+                                     uint8_t* q_t, int64_t ldqt,
+                                     float* s_t, int64_t st_stride_col, int64_t st_stride_tb, void* stream);
+ds3_status ds3_retile_1x128_to_128x1_pow2(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq,
+                                          const float* s, int64_t s_stride_row, int64_t s_stride_kb,
+                                          uint8_t* q_t, int64_t ldqt,
+                                          float* s_t, int64_t st_stride_col, int64_t st_stride_tb, void* stream);
+
+/*
  * SwiGLU fused with the 1x128 quantization of its output (Section 3.3.3,
  * Low-Precision Activation: the down projection takes the SwiGLU output
  * quantized to FP8; Section 3.5.2 asks for the cast to be fused with the

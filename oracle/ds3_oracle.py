@@ -249,3 +249,13 @@ def swiglu_quant_1x128(h, pow2: bool = False):
     from the FP32 evaluation), quantized per 1x128 tile.  Defined as the
     composition of the two steps, which is what a fused kernel must equal."""
     return quant_act_1x128(round_to_bf16(swiglu(h)), pow2=pow2)
+
+
+def retile_1x128_to_128x1(q, s, pow2: bool = False):
+    """Re-tile a cached FP8 activation for the weight-gradient GEMM (Section
+    3.5.2, transposed GEMM operations; Section 3.3.3 (1)): the 1x128-quantized
+    matrix [T][C] is dequantized (one FP32 multiply per element), transposed,
+    and re-quantized into 128x1 tiles along the token axis.  Returns what
+    quant_act_128x1 returns: codes [C][T] and scales [C][ceil(T/128)]."""
+    v = dequant_rows(q, s).astype(np.float32)          # dec(q) * s is exact in FP64, so this is ONE FP32 rounding
+    return quant_act_128x1(v, pow2=pow2)

@@ -28,6 +28,7 @@ SYMBOLS = [
     "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
+    "ds3_retile_1x128_to_128x1", "ds3_retile_1x128_to_128x1_pow2",
 ]
 
 
@@ -59,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
     lib.ds3_swiglu_quant_1x128.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_swiglu_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_retile_1x128_to_128x1.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_retile_1x128_to_128x1_pow2.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
@@ -281,6 +284,28 @@ def ds3_swiglu_quant_1x128(h: torch.Tensor, k_major_scales: bool = True):
 def ds3_swiglu_quant_1x128_pow2(h: torch.Tensor, k_major_scales: bool = True):
     """As ds3_swiglu_quant_1x128 with power-of-two scales."""
     return _swiglu_quant("ds3_swiglu_quant_1x128_pow2", h, k_major_scales)
+
+
+def _retile(entry: str, q: torch.Tensor, s: torch.Tensor, k_major_scales: bool):
+    t, c, ldq = _rows2d(q, "q")
+    if q.dtype != torch.uint8 or s.dtype != torch.float32 or tuple(s.shape) != (t, (c + 127) // 128):
+        raise ValueError("q: uint8 [T][C]; s: float32 logical [T][ceil(C/128)]")
+    q_t = _codes(c, t, q.device)
+    s_t = _scales(c, (t + 127) // 128, q.device, k_major_scales)
+    st = getattr(_L(), entry)(q.data_ptr(), t, c, ldq, s.data_ptr(), s.stride(0), s.stride(1), q_t.data_ptr(),
+                              (t + 15) // 16 * 16, s_t.data_ptr(), s_t.stride(0), s_t.stride(1), _stream())
+    _check(st, entry)
+    return q_t, s_t
+
+
+def ds3_retile_1x128_to_128x1(q: torch.Tensor, s: torch.Tensor, k_major_scales: bool = True):
+    """1x128-quantized [T][C] (codes, scales) -> 128x1-quantized, transposed: (codes [C][T], scales [C][ceil(T/128)])."""
+    return _retile("ds3_retile_1x128_to_128x1", q, s, k_major_scales)
+
+
+def ds3_retile_1x128_to_128x1_pow2(q: torch.Tensor, s: torch.Tensor, k_major_scales: bool = True):
+    """As ds3_retile_1x128_to_128x1 with power-of-two output scales."""
+    return _retile("ds3_retile_1x128_to_128x1_pow2", q, s, k_major_scales)
 
 
 def ds3_gemm_num_variants() -> int:

@@ -23,6 +23,7 @@ def _quant_bytes(rows, cols, groups):
 
 
 _UNFUSED_SWIGLU = False
+_WGRAD_FROM_CACHE = False
 
 
 class _Pow2:
@@ -32,15 +33,15 @@ class _Pow2:
         self._ds3 = ds3
 
     def __getattr__(self, name):
-        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_swiglu_quant")) \
+        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_swiglu_quant", "ds3_retile_")) \
                 and not name.endswith("_pow2"):
             return getattr(self._ds3, name + "_pow2")
         return getattr(self._ds3, name)
 
 
-def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False):
-    global _UNFUSED_SWIGLU
-    _UNFUSED_SWIGLU = unfused_swiglu
+def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False, wgrad_from_cache=False):
+    global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE
+    _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE = unfused_swiglu, wgrad_from_cache
     step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](
         _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
     if pow2:
@@ -146,6 +147,11 @@ def _cfg4(ds3, torch, wl, dev, variant):
     def q_x_col():
         st["qxt"], st["sxt"] = ds3.ds3_quant_act_128x1(x)
 
+    qx_cache, sx_cache = ds3.ds3_quant_act_1x128(x)                      # what Fprop left behind
+
+    def retile_x():
+        st["qxt"], st["sxt"] = ds3.ds3_retile_1x128_to_128x1(qx_cache, sx_cache)
+
     def wgrad():
         ds3.ds3_gemm_fp8_bs(st["qdyt"], st["sdyt"], st["qxt"], st["sxt"], sb_mode=ds3.DS3_BSCALE_PER_ROW, c=dw,
                             accumulate=True, variant=variant)
@@ -159,6 +165,10 @@ def _cfg4(ds3, torch, wl, dev, variant):
         Timed("quant_act_128x1(X)", q_x_col, "GB/s", _quant_bytes(M, K, M * K // 128) / 1e9, "hbm", PEAK_HBM_GBS),
         Timed("gemm_fp8_bs(wgrad, fp32 accumulate)", wgrad, "TFLOP/s", fl / 1e12, "mfma", PEAK_FP8_TFLOPS),
     ]
+    if _WGRAD_FROM_CACHE:
+        # X comes from the FP8 1x128 cache of the forward pass: 1 B read + 1 B written per element, scales both ways
+        kernels[4] = Timed("retile_1x128_to_128x1(X cache)", retile_x, "GB/s", (M * K * 2 + 2 * (M * K // 128) * 4) / 1e9,
+                           "hbm", PEAK_HBM_GBS)
 
     def step(record):
         for k in kernels:
@@ -166,7 +176,8 @@ def _cfg4(ds3, torch, wl, dev, variant):
 
     cfg = {"workload": "cfg4: backward of the cfg2 layer; Dgrad dX[4096x7168] = dY[4096x18432] W (dY 1x128, W^T 128x128) "
                        "and Wgrad dW[18432x7168] += dY^T X over 4096 tokens (both operands 128x1), dW FP32",
-           "M": M, "N": N, "K": K, "gemm_variant": variant}
+           "M": M, "N": N, "K": K, "gemm_variant": variant,
+           "wgrad_x_source": "FP8 1x128 cache, re-tiled" if _WGRAD_FROM_CACHE else "BF16 X, quantized along tokens"}
     return step, kernels, 2 * fl, cfg, "gemm_fp8_bs(dgrad)"
 
 

@@ -197,6 +197,29 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, v
     return launch_swiglu(h, rows, inter, ldh, out, ldo, static_cast<hipStream_t>(stream));
 }
 
+static ds3_status retile(int pow2, const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s, int64_t ssr,
+                         int64_t ssk, uint8_t* q_t, int64_t ldqt, float* s_t, int64_t ssc, int64_t sst, void* stream) {
+    if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return DS3_OK;
+    if (!q || !s || !q_t || !s_t) return DS3_ERR_NULL;
+    if (ldq < cols || ldqt < rows) return DS3_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(q_t) || cols % 16 || ldq % 16 || ldqt % 16) return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || cols > kMaxDim || (rows + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_retile_1x128_to_128x1(q, rows, cols, ldq, s, ssr, ssk, q_t, ldqt, s_t, ssc, sst, pow2,
+                                        static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s,
+                                     int64_t s_stride_row, int64_t s_stride_kb, uint8_t* q_t, int64_t ldqt, float* s_t,
+                                     int64_t st_stride_col, int64_t st_stride_tb, void* stream) {
+    return retile(0, q, rows, cols, ldq, s, s_stride_row, s_stride_kb, q_t, ldqt, s_t, st_stride_col, st_stride_tb, stream);
+}
+ds3_status ds3_retile_1x128_to_128x1_pow2(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s,
+                                          int64_t s_stride_row, int64_t s_stride_kb, uint8_t* q_t, int64_t ldqt,
+                                          float* s_t, int64_t st_stride_col, int64_t st_stride_tb, void* stream) {
+    return retile(1, q, rows, cols, ldq, s, s_stride_row, s_stride_kb, q_t, ldqt, s_t, st_stride_col, st_stride_tb, stream);
+}
+
 static ds3_status swiglu_quant(int pow2, const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
                                float* s, int64_t ssr, int64_t ssk, void* stream) {
     if (rows < 0 || inter < 0) return DS3_ERR_SHAPE;

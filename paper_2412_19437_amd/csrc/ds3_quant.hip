@@ -294,6 +294,108 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const uint8_t* __restrict__
 }
 
 // =============================================================================
+// Re-tiling of a cached FP8 activation for the weight-gradient GEMM: 1x128
+// tiles [T][C] -> 128x1 tiles written transposed [C][T].  Same workgroup shape
+// as the 128x1 quantizer (128 tokens x 128 channels), but the source is one
+// byte per element plus one scale per token: a thread owns 16 channels of 4
+// consecutive tokens, dequantizes them with one FP32 multiply each (the same
+// values for the max-abs pass and for the cast), and packs the 4 tokens of a
+// channel into one word of the [channel][token] LDS tile.
+// =============================================================================
+__device__ __forceinline__ void dec4_e4m3(unsigned int w, float* v) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    v[0] = lo.x; v[1] = lo.y; v[2] = hi.x; v[3] = hi.y;
+}
+
+__global__ __launch_bounds__(256) void retile_1x128_to_128x1_kernel(
+    const uint8_t* __restrict__ q, int64_t rows, int64_t cols, int64_t ldq,
+    const float* __restrict__ s, int64_t ssr, int64_t ssk,
+    uint8_t* __restrict__ qt, int64_t ldqt, float* __restrict__ st, int64_t ssc, int64_t sst, int pow2) {
+    constexpr int LPR = 8;                        // lanes across the 128 channels (16 codes each)
+    constexpr int NSL = 32;                       // token slices
+    constexpr int TPT = 4;                        // consecutive tokens per thread
+    constexpr int OST = 128 + 16;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[128 * OST];
+    __shared__ float rmul[128];
+    static_assert(NSL * 128 * 4 <= 128 * OST, "partial maxima fit in the code tile");
+    unsigned int (*part)[128] = reinterpret_cast<unsigned int (*)[128]>(tile);
+
+    const int64_t c0 = (int64_t)blockIdx.x * 128, t0 = (int64_t)blockIdx.y * 128;
+    const int lc = threadIdx.x % LPR, sl = threadIdx.x / LPR;
+    const int64_t col = c0 + lc * 16;
+    const bool col_ok = col < cols;
+
+    u32x4 g[TPT];
+    float sc[TPT];
+#pragma unroll
+    for (int p = 0; p < TPT; ++p) {
+        const int64_t tok = t0 + sl * TPT + p;
+        g[p] = u32x4{0u, 0u, 0u, 0u};
+        sc[p] = 0.f;
+        if (col_ok && tok < rows) {
+            g[p] = ld_stream(q + tok * ldq + col);
+            sc[p] = s[tok * ssr + (int64_t)blockIdx.x * ssk];
+        }
+    }
+    // per-channel max over this thread's 4 tokens
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        unsigned int cm[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int p = 0; p < TPT; ++p) {
+            float v[4];
+            dec4_e4m3(g[p][w], v);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cm[i] = umax(cm[i], as_u32(v[i] * sc[p]) & 0x7fffffffu);
+        }
+        *reinterpret_cast<u32x4*>(&part[sl][lc * 16 + w * 4]) = u32x4{cm[0], cm[1], cm[2], cm[3]};
+    }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        unsigned int m = 0;
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) m = umax(m, part[j][threadIdx.x]);
+        const GroupScale gs = group_scale(as_f32(m), pow2);
+        rmul[threadIdx.x] = gs.r;
+        if (c0 + threadIdx.x < cols) st[(c0 + threadIdx.x) * ssc + (int64_t)blockIdx.y * sst] = gs.s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        float y[TPT][4];
+#pragma unroll
+        for (int p = 0; p < TPT; ++p) {
+            dec4_e4m3(g[p][w], y[p]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[p][i] = y[p][i] * sc[p];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float r = rmul[lc * 16 + w * 4 + i];
+            *reinterpret_cast<unsigned int*>(tile + (lc * 16 + w * 4 + i) * OST + sl * TPT) =
+                cvt4_e4m3(y[0][i] * r, y[1][i] * r, y[2][i] * r, y[3][i] * r);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int ch = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
+        const int64_t tok = t0 + chunk * 16;
+        if (c0 + ch >= cols || tok >= rows) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + ch * OST + chunk * 16);
+        uint8_t* dst = qt + (c0 + ch) * ldqt + tok;
+        if (tok + 16 <= rows) {
+            st_stream(dst, v);
+        } else {
+            const unsigned int wds[4] = {v.x, v.y, v.z, v.w};
+            for (int b = 0; b < 16 && tok + b < rows; ++b) dst[b] = (uint8_t)(wds[b >> 2] >> (8 * (b & 3)));
+        }
+    }
+}
+
+// =============================================================================
 // SwiGLU fused with the 1x128 quantizer of the down projection's input: the
 // activation is rounded to BF16 exactly as swiglu_kernel writes it, but goes
 // straight from registers into the max-abs / scale / cast steps of the 1x128
@@ -417,6 +519,14 @@ ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh
     const int64_t n = rows * (inter / 8);
     swiglu_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>((const uint8_t*)h, rows, inter, ldh * 2,
                                                                      (uint8_t*)out, ldo * 2);
+    return launch_status();
+}
+
+ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s,
+                                        int64_t ssr, int64_t ssk, uint8_t* qt, int64_t ldqt, float* s_t, int64_t ssc,
+                                        int64_t sst, int pow2, hipStream_t st) {
+    dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
+    retile_1x128_to_128x1_kernel<<<grid, 256, 0, st>>>(q, rows, cols, ldq, s, ssr, ssk, qt, ldqt, s_t, ssc, sst, pow2);
     return launch_status();
 }
 

@@ -162,3 +162,38 @@ def test_grouped_pow2(ds3):
         announce(f"pow2 grouped variant {v}")
         c = host(ds3.ds3_grouped_gemm_fp8_bs_pow2(dev(a), _kmajor(sa), dev(off), dev(b), dev(sb), out_dtype=torch.float32, variant=v))
         assert np.array_equal(c.astype(np.float64), ref), v
+
+
+@pytest.mark.parametrize("pow2", [False, True])
+@pytest.mark.parametrize("k_major", [True, False])
+@pytest.mark.parametrize("shape", [(512, 1024), (300, 208), (4096, 256), (1, 16), (131, 2048)])
+def test_retile_cached_activation(ds3, shape, k_major, pow2):
+    """FP8 1x128 cache -> 128x1 tiles (Section 3.5.2), bit for bit against the oracle on
+    the same cached codes and scales; the cache itself comes from the GPU quantizer of
+    matching kind (checked against the oracle elsewhere)."""
+    announce(f"retile {shape} k_major={k_major} pow2={pow2}")
+    x = wl.cfg2_x(m=shape[0], k=shape[1])
+    q, s = (ds3.ds3_quant_act_1x128_pow2 if pow2 else ds3.ds3_quant_act_1x128)(dev(x, bf16=True), k_major_scales=k_major)
+    fn = ds3.ds3_retile_1x128_to_128x1_pow2 if pow2 else ds3.ds3_retile_1x128_to_128x1
+    qt, st = fn(q, s, k_major_scales=k_major)
+    qt_ref, st_ref = orc.retile_1x128_to_128x1(host(q), host(s), pow2=pow2)
+    _same(qt, st, qt_ref, st_ref, "retile")
+
+
+def test_wgrad_from_retiled_cache(ds3):
+    """The weight-gradient GEMM fed from the re-tiled FP8 cache of X (and dY quantized
+    along tokens from BF16) against the FP64 oracle on the same codes."""
+    announce("wgrad from cache")
+    t, n_out, n_in = 512, 256, 384
+    x, dy = wl.cfg2_x(m=t, k=n_in), wl.normal((t, n_out), 1e-2, 761)
+    qx, sx = ds3.ds3_quant_act_1x128(dev(x, bf16=True))                   # what Fprop cached
+    qxt, sxt = ds3.ds3_retile_1x128_to_128x1(qx, sx)
+    qyt, syt = ds3.ds3_quant_act_128x1(dev(dy, bf16=True))
+    ref = orc.gemm_fp8_bs(host(qyt), host(syt), host(qxt), host(sxt), sb_per_row=True)
+    dw = host(ds3.ds3_gemm_fp8_bs(qyt, syt, qxt, sxt, sb_mode=ds3.DS3_BSCALE_PER_ROW, out_dtype=torch.float32))
+    assert normwise(dw, ref) <= TOL_F32
+    # the extra quantization step costs accuracy against the unquantized gradient, within a few percent
+    exact = dy.astype(np.float64).T @ x.astype(np.float64)
+    e = normwise(dw, exact)
+    print("wgrad from re-tiled cache vs unquantized:", e)
+    assert e < 0.06

@@ -142,3 +142,63 @@ def test_zero_group_and_ragged_tail():
     assert s.shape == (2, 2) and s[0, 0] == 1.0 and s[0, 1] == 1.0 and s[1, 0] == 1.0
     assert s[1, 1] == np.float32(2.0 ** -7)                    # 3/448 = 0.0067 <= 2^-7 = 0.0078
     assert q[1, 130] == 0x80 | orc.e4m3_encode_rne_sat(np.array([384.0], np.float32))[0]
+
+
+# ---- re-tiling of a cached 1x128 activation into 128x1 tiles (Section 3.5.2) ----
+def _fl32(fr: Fraction) -> Fraction:
+    if fr == 0:
+        return Fraction(0)
+    a = abs(fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    q = Fraction(2) ** (e - 23)
+    n = a / q
+    fl = n.numerator // n.denominator
+    rem = n - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    return (-1 if fr < 0 else 1) * fl * q
+
+
+def test_retile_vs_exact_rational_implementation():
+    """Dequantize with exact rationals rounded once to FP32, then the general 128x1
+    rule (correctly rounded amax/448 and 448/amax, one FP32 multiply, nearest-even cast)."""
+    x = wl.cfg2_x(m=128, k=256)[:, 120:136].copy()            # 16 channels straddling two 1x128 tiles
+    xp = np.zeros((128, 256), np.float32); xp[:, 120:136] = x
+    q, s = orc.quant_act_1x128(xp)
+    qt, st = orc.retile_1x128_to_128x1(q, s)
+    for c in (120, 127, 128, 135):
+        v = [_fl32(_TABLE[q[t, c] & 0x7F] * (-1 if q[t, c] & 0x80 else 1) * Fraction(float(s[t, c // 128]))) for t in range(128)]
+        amax = max(abs(f) for f in v)
+        sc, r = _fl32(amax / 448), _fl32(Fraction(448) / amax)
+        assert Fraction(float(st[c, 0])) == sc
+        codes = [_enc(_fl32(f * r), bool(q[t, c] & 0x80)) for t, f in enumerate(v)]
+        assert list(qt[c]) == codes, c
+
+
+def test_retile_identities():
+    x = wl.cfg2_x(m=256, k=256)
+    q, s = orc.quant_act_1x128(x)
+    qt, st = orc.retile_1x128_to_128x1(q, s)
+    assert qt.shape == (256, 256) and st.shape == (256, 2)
+    # it is the 128x1 quantizer applied to the dequantized cache ...
+    v = (orc.e4m3_decode(q).astype(np.float64) * np.repeat(s.astype(np.float64), 128, axis=1)).astype(np.float32)
+    q2, s2 = orc.quant_act_128x1(v)
+    assert np.array_equal(qt, q2) and np.array_equal(st, s2)
+    # ... whose group maxima are reproduced by the new tiles: max |dequant| per (channel, token block) is kept
+    back = orc.dequant_rows(qt, st).T
+    for tb in range(2):
+        blk = slice(tb * 128, (tb + 1) * 128)
+        assert np.allclose(np.abs(back[blk]).max(axis=0), np.abs(v[blk].astype(np.float64)).max(axis=0), rtol=2e-7)
+    # a matrix whose rows are all equal has one value per channel: every 128x1 tile is constant, code 0x7E
+    row = wl.cfg2_x(m=1, k=256)
+    q1, s1 = orc.quant_act_1x128(np.repeat(row, 128, axis=0))
+    qt1, _ = orc.retile_1x128_to_128x1(q1, s1)
+    nz = (q1[0] & 0x7F) != 0
+    assert np.all((qt1[nz] & 0x7F) == 0x7E)
+    # ragged token count and an all-zero channel
+    q3, s3 = orc.quant_act_1x128(x[:130])
+    q3[:, 7] = 0
+    qt3, st3 = orc.retile_1x128_to_128x1(q3, s3)
+    assert qt3.shape == (256, 130) and st3.shape == (256, 2) and st3[7, 0] == 1.0 and st3[7, 1] == 1.0
