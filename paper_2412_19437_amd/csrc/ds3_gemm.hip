@@ -49,6 +49,12 @@ struct Cfg {
     static constexpr int STAGE = ROWS * 128;           // bytes of codes per K-step
     static constexpr int RPI = NT / 8;                 // tile rows one load instruction of the workgroup covers
     static constexpr int LPT = ROWS / RPI;             // 16-byte loads per thread per K-step
+#ifndef DS3_TAIL_LOADS
+#define DS3_TAIL_LOADS (LPT < FN ? LPT : FN)
+#endif
+    // loads of a K-step that are issued right behind the barrier that frees their stage (the
+    // rest go out at the head of the next K-step)
+    static constexpr int TAILN = (DS3_TAIL_LOADS) < LPT ? (DS3_TAIL_LOADS) : LPT;
     static constexpr int SCALE_BYTES = 2 * NS * NT * 4;        // [NS][NT] sa + [NS][NT] per-row sb
     static constexpr int LDS_BYTES = NS * STAGE + SCALE_BYTES + (kMaxGroups + 1) * 4;   // + row-tile prefix of the experts
     // workgroups that fit one compute unit: 160 KiB of LDS, and two waves per SIMD (the
@@ -264,7 +270,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         __syncthreads();
         // the part of K-step NS-1 that a previous K-step's barrier would have issued
 #pragma unroll
-        for (int i = 0; i < (C::LPT < FN ? C::LPT : FN); ++i)
+        for (int i = 0; i < C::TAILN; ++i)
             issue_load(cur, i, NS - 1, NS - 1 < KB ? (unsigned)(NS - 1) << 7 : kOobOffset);
         float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
         float tj[FM];
@@ -290,7 +296,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         // The stage a barrier frees is refilled at once: the first TAILN loads of the
         // K-step NS steps ahead go out behind the barrier, one per sub-tile of the last
         // activation fragment, the rest at the head of the next K-step.
-        constexpr int TAILN = C::LPT < FN ? C::LPT : FN;   // loads issued right behind the barrier
+        constexpr int TAILN = C::TAILN;                    // loads issued right behind the barrier
         constexpr int HEADN = C::LPT - TAILN;              // loads issued at the head of the following K-step
         static_assert(HEADN <= NSUB - FN, "not enough sub-tiles before the barrier for the head loads");
         auto kstep = [&](int kb, auto stage_tag) {
@@ -331,7 +337,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     if (j == FM - 1) {
                         // last activation fragment: refill this weight fragment for the next K-step
                         pf[i] = load_frag(nst + p_base + i * 2048);
-                        if (i < TAILN) issue_load(cur, i, S, koff2);
+#pragma unroll
+                        for (int l = i; l < TAILN; l += FN) issue_load(cur, l, S, koff2);
                         if (i == FN - 1) {
                             qf[0] = load_frag(nst + q_base);
                             read_tj(SN, sb_n, tjn);
@@ -398,7 +405,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                                                                              0, eb[j]);
                 if (j == FM - 1) {
                     pf[i] = load_frag(nst + p_base + i * 2048);
-                    if (i < TAILN) issue_load(cur, i, S, koff2);
+#pragma unroll
+                    for (int l = i; l < TAILN; l += FN) issue_load(cur, l, S, koff2);
                     if (i == FN - 1) {
                         qf[0] = load_frag(nst + q_base);
                         read_tj(SN, 1.f, tjn);
