@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--unfused-swiglu", action="store_true", help="cfg3: separate SwiGLU and 1x128 quantizer kernels")
     ap.add_argument("--wgrad-from-cache", action="store_true",
                     help="cfg4: the Wgrad activation operand is re-tiled from the FP8 1x128 cache instead of re-quantized from BF16")
+    ap.add_argument("--dual-weight-quant", action="store_true",
+                    help="cfg4: the Dgrad weight codes come from the quantizer that writes W and W^T from one read of W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the two machine probes (sustained MFMA rate, L2->LDS feed)")
     ap.add_argument("--gemm-variant", type=int, default=-1)
@@ -212,7 +214,8 @@ def main():
     if args.workload != "cfg2":
         from paper_2412_19437_amd import bench_extra
         step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant,
-                                                                args.pow2, args.unfused_swiglu, args.wgrad_from_cache)
+                                                                args.pow2, args.unfused_swiglu, args.wgrad_from_cache,
+                                                                args.dual_weight_quant)
     else:
         step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant, args.pow2)
 

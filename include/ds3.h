@@ -238,6 +238,23 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
                       void* out, int64_t ldo, void* stream);
 
 /*
+ * 128x128 weight quantizer that also writes the transposed codes, the weight
+ * operand of Dgrad (Section 3.3.1: dX = dY W contracts over W's rows; the
+ * 128x128 blocks and their scales are transpose-invariant, so W^T needs no
+ * second quantization -- Appendix B.2 makes the same point for block-wise
+ * tiles: "only transposition is required").  One read of W, two layouts:
+ *   q    [n][ldq]   and  s    [ceil(n/128)][ceil(k/128)]   as ds3_quant_w_128x128
+ *   q_t  [k][ldqt]  and  s_t  [ceil(k/128)][ceil(n/128)]:  q_t[c][r] = q[r][c], s_t[j][i] = s[i][j]
+ * Alignment as ds3_quant_w_128x128, plus q_t 16-byte aligned and ldqt % 16 == 0.
+ */
+ds3_status ds3_quant_w_128x128_dual(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw,
+                                    uint8_t* q, int64_t ldq, float* s,
+                                    uint8_t* q_t, int64_t ldqt, float* s_t, void* stream);
+ds3_status ds3_quant_w_128x128_dual_pow2(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw,
+                                         uint8_t* q, int64_t ldq, float* s,
+                                         uint8_t* q_t, int64_t ldqt, float* s_t, void* stream);
+
+/*
  * Re-tiling of a cached FP8 activation for the weight-gradient GEMM (Section
  * 3.5.2, Support for Transposed GEMM Operations: the activation kept from the
  * forward pass in 1x128 tiles is read back, dequantized, transposed and

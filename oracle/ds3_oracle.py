@@ -259,3 +259,14 @@ def retile_1x128_to_128x1(q, s, pow2: bool = False):
     quant_act_128x1 returns: codes [C][T] and scales [C][ceil(T/128)]."""
     v = dequant_rows(q, s).astype(np.float32)          # dec(q) * s is exact in FP64, so this is ONE FP32 rounding
     return quant_act_128x1(v, pow2=pow2)
+
+
+def quant_w_128x128_dual(w, pow2: bool = False):
+    """The weight and its transpose, both 128x128-quantized (Section 3.3.1: Fprop
+    uses W, Dgrad contracts over W's rows and needs W^T).  Each is quantized on its
+    own here; that the second result is the transpose of the first is a property
+    of block-wise tiles (Appendix B.2) which the tests pin rather than assume."""
+    w = np.asarray(w)
+    q, s = quant_w_128x128(w, pow2=pow2)
+    q_t, s_t = quant_w_128x128(np.ascontiguousarray(w.T), pow2=pow2)
+    return q, s, q_t, s_t

@@ -29,6 +29,7 @@ SYMBOLS = [
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
     "ds3_retile_1x128_to_128x1", "ds3_retile_1x128_to_128x1_pow2",
+    "ds3_quant_w_128x128_dual", "ds3_quant_w_128x128_dual_pow2",
 ]
 
 
@@ -62,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.ds3_swiglu_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1_pow2.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_quant_w_128x128_dual.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i64, vp, vp]
+    lib.ds3_quant_w_128x128_dual_pow2.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i64, vp, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
@@ -261,6 +264,28 @@ def ds3_swiglu(h: torch.Tensor):
     st = _L().ds3_swiglu(h.data_ptr(), rows, two_i // 2, ldh, out.data_ptr(), two_i // 2, _stream())
     _check(st, "ds3_swiglu")
     return out
+
+
+def _quant_w_dual(entry: str, w: torch.Tensor):
+    n, k, ldw = _rows2d(w, "w")
+    q, q_t = _codes(n, k, w.device), _codes(k, n, w.device)
+    nb, kb = (n + 127) // 128, (k + 127) // 128
+    s = torch.empty((nb, kb), dtype=torch.float32, device=w.device)
+    s_t = torch.empty((kb, nb), dtype=torch.float32, device=w.device)
+    st = getattr(_L(), entry)(w.data_ptr(), _dt(w), n, k, ldw, q.data_ptr(), (k + 15) // 16 * 16, s.data_ptr(),
+                              q_t.data_ptr(), (n + 15) // 16 * 16, s_t.data_ptr(), _stream())
+    _check(st, entry)
+    return q, s, q_t, s_t
+
+
+def ds3_quant_w_128x128_dual(w: torch.Tensor):
+    """w [N][K] -> (codes [N][K], scales [N/128][K/128], codes of the transpose [K][N], its scales [K/128][N/128])."""
+    return _quant_w_dual("ds3_quant_w_128x128_dual", w)
+
+
+def ds3_quant_w_128x128_dual_pow2(w: torch.Tensor):
+    """As ds3_quant_w_128x128_dual with power-of-two scales."""
+    return _quant_w_dual("ds3_quant_w_128x128_dual_pow2", w)
 
 
 def _swiglu_quant(entry: str, h: torch.Tensor, k_major_scales: bool):

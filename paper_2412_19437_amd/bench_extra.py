@@ -24,6 +24,7 @@ def _quant_bytes(rows, cols, groups):
 
 _UNFUSED_SWIGLU = False
 _WGRAD_FROM_CACHE = False
+_DUAL_WEIGHT_QUANT = False
 
 
 class _Pow2:
@@ -39,9 +40,10 @@ class _Pow2:
         return getattr(self._ds3, name)
 
 
-def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False, wgrad_from_cache=False):
-    global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE
-    _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE = unfused_swiglu, wgrad_from_cache
+def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False, wgrad_from_cache=False,
+          dual_weight_quant=False):
+    global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT
+    _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT = unfused_swiglu, wgrad_from_cache, dual_weight_quant
     step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](
         _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
     if pow2:
@@ -138,6 +140,11 @@ def _cfg4(ds3, torch, wl, dev, variant):
     def q_wt():
         st["qwt"], st["swt"] = ds3.ds3_quant_w_128x128(wt)
 
+    w_fwd = _bf16(torch, wl.cfg2_w(), dev) if _DUAL_WEIGHT_QUANT else None   # W [N][K] as the forward pass holds it
+
+    def q_w_dual():
+        _, _, st["qwt"], st["swt"] = ds3.ds3_quant_w_128x128_dual(w_fwd)
+
     def dgrad():
         st["dx"] = ds3.ds3_gemm_fp8_bs(st["qdy"], st["sdy"], st["qwt"], st["swt"], variant=variant)
 
@@ -165,6 +172,10 @@ def _cfg4(ds3, torch, wl, dev, variant):
         Timed("quant_act_128x1(X)", q_x_col, "GB/s", _quant_bytes(M, K, M * K // 128) / 1e9, "hbm", PEAK_HBM_GBS),
         Timed("gemm_fp8_bs(wgrad, fp32 accumulate)", wgrad, "TFLOP/s", fl / 1e12, "mfma", PEAK_FP8_TFLOPS),
     ]
+    if _DUAL_WEIGHT_QUANT:
+        # one read of W, codes written in both layouts: 2 + 1 + 1 bytes per element
+        kernels[1] = Timed("quant_w_128x128_dual(W -> W, W^T)", q_w_dual, "GB/s", (K * N * 4 + 2 * (K * N // 16384) * 4) / 1e9,
+                           "hbm", PEAK_HBM_GBS)
     if _WGRAD_FROM_CACHE:
         # X comes from the FP8 1x128 cache of the forward pass: 1 B read + 1 B written per element, scales both ways
         kernels[4] = Timed("retile_1x128_to_128x1(X cache)", retile_x, "GB/s", (M * K * 2 + 2 * (M * K // 128) * 4) / 1e9,
@@ -177,6 +188,7 @@ def _cfg4(ds3, torch, wl, dev, variant):
     cfg = {"workload": "cfg4: backward of the cfg2 layer; Dgrad dX[4096x7168] = dY[4096x18432] W (dY 1x128, W^T 128x128) "
                        "and Wgrad dW[18432x7168] += dY^T X over 4096 tokens (both operands 128x1), dW FP32",
            "M": M, "N": N, "K": K, "gemm_variant": variant,
+           "dgrad_weight_codes": "from the dual-layout quantizer of W" if _DUAL_WEIGHT_QUANT else "quantizer run on a materialised W^T",
            "wgrad_x_source": "FP8 1x128 cache, re-tiled" if _WGRAD_FROM_CACHE else "BF16 X, quantized along tokens"}
     return step, kernels, 2 * fl, cfg, "gemm_fp8_bs(dgrad)"
 

@@ -197,6 +197,26 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, v
     return launch_swiglu(h, rows, inter, ldh, out, ldo, static_cast<hipStream_t>(stream));
 }
 
+static ds3_status quant_dual(int pow2, const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                             int64_t ldq, float* s, uint8_t* q_t, int64_t ldqt, float* s_t, void* stream) {
+    const ds3_status st = check_quant(w, wt, n, k, ldw, q, k, ldq, s);
+    if (st != DS3_OK || n == 0 || k == 0) return st;
+    if (!q_t || !s_t) return DS3_ERR_NULL;
+    if (ldqt < n) return DS3_ERR_SHAPE;
+    if (!aligned16(q_t) || ldqt % 16) return DS3_ERR_ALIGN;
+    if ((n + 127) / 128 > 65535) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_w_128x128_dual(w, wt, n, k, ldw, q, ldq, s, q_t, ldqt, s_t, pow2, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_quant_w_128x128_dual(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q, int64_t ldq,
+                                    float* s, uint8_t* q_t, int64_t ldqt, float* s_t, void* stream) {
+    return quant_dual(0, w, wt, n, k, ldw, q, ldq, s, q_t, ldqt, s_t, stream);
+}
+ds3_status ds3_quant_w_128x128_dual_pow2(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                         int64_t ldq, float* s, uint8_t* q_t, int64_t ldqt, float* s_t, void* stream) {
+    return quant_dual(1, w, wt, n, k, ldw, q, ldq, s, q_t, ldqt, s_t, stream);
+}
+
 static ds3_status retile(int pow2, const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s, int64_t ssr,
                          int64_t ssk, uint8_t* q_t, int64_t ldqt, float* s_t, int64_t ssc, int64_t sst, void* stream) {
     if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;

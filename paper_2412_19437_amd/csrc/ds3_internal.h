@@ -13,6 +13,9 @@ ds3_status launch_quant_act_128x1(const void* x, ds3_dtype xt, int64_t rows, int
                                   int64_t ldq, float* s_t, int64_t ssc, int64_t sst, int pow2, hipStream_t st);
 ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
                                   int64_t ldq, float* s, int pow2, hipStream_t st);
+ds3_status launch_quant_w_128x128_dual(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                       int64_t ldq, float* s, uint8_t* qt, int64_t ldqt, float* s_t, int pow2,
+                                       hipStream_t st);
 ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo,
                          hipStream_t st);
 

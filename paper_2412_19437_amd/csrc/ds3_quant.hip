@@ -170,6 +170,102 @@ __global__ __launch_bounds__(256) void quant_w_128x128_kernel(
 }
 
 // =============================================================================
+// 128x128 with both layouts from one read: the codes of W [n][k] and of its
+// transpose [k][n] (the Dgrad operand; a 128x128 block and its scale are
+// transpose-invariant, so the transposed codes are the same bytes moved).
+// A thread owns RPT consecutive rows of one 16-byte granule, so for every one of
+// its columns it holds RPT consecutive codes of the transposed row; those go
+// through an LDS tile [k][n] and leave as 16-byte stores.
+// =============================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void quant_w_128x128_dual_kernel(
+    const uint8_t* __restrict__ w, int64_t n, int64_t k, int64_t ldw_bytes,
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s,
+    uint8_t* __restrict__ qt, int64_t ldqt, float* __restrict__ st, int64_t nkb, int64_t nnb, int pow2) {
+    constexpr int EPL = T::EPL;
+    constexpr int ESZ = 16 / EPL;
+    constexpr int LPR = 128 / EPL;                // lanes per block row
+    constexpr int NRG = 256 / LPR;                // row groups
+    constexpr int RPT = 128 / NRG;                // consecutive rows per thread (8 BF16, 16 FP32)
+    constexpr int OST = 128 + 16;
+    __shared__ unsigned int red[16];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[128 * OST];   // [k][n]
+    const int64_t kb = blockIdx.x, nb = blockIdx.y;
+    const int lc = threadIdx.x % LPR, rg = threadIdx.x / LPR;
+    const int64_t col = kb * 128 + lc * EPL;
+    const bool col_ok = col < k;
+
+    u32x4 g[RPT];
+    unsigned int m = 0;
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int64_t row = nb * 128 + rg * RPT + r;
+        g[r] = u32x4{0u, 0u, 0u, 0u};
+        if (col_ok && row < n) g[r] = ld_stream(w + row * ldw_bytes + col * ESZ);
+    }
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) m = umax(m, granule_amax_bits<T>(g[r]));
+    m = row16_max_bits(m);
+    if ((threadIdx.x & 15) == 0) red[threadIdx.x >> 4] = m;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m = umax(m, red[i]);
+    const GroupScale gs = group_scale(as_f32(m), pow2);
+    if (threadIdx.x == 0) {
+        s[nb * nkb + kb] = gs.s;
+        st[kb * nnb + nb] = gs.s;
+    }
+    // codes of this thread: cw[r][j] = word j (4 consecutive columns) of row r
+    unsigned int cw[RPT][EPL / 4];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int64_t row = nb * 128 + rg * RPT + r;
+        float v[EPL];
+        widen<T>(g[r], v);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) v[i] = v[i] * gs.r;
+#pragma unroll
+        for (int j = 0; j < EPL / 4; ++j) cw[r][j] = cvt4_e4m3(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+        if (col_ok && row < n) {
+            uint8_t* dst = q + row * ldq + col;
+            if constexpr (EPL == 8) st_stream(dst, u32x2{cw[r][0], cw[r][1]});
+            else st_stream(dst, cw[r][0]);
+        }
+    }
+    // transposed: for column e of the granule, the RPT codes of rows rg*RPT .. are consecutive in [k][n]
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+        unsigned int tw[RPT / 4];
+#pragma unroll
+        for (int x = 0; x < RPT / 4; ++x) {
+            unsigned int wv = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) wv |= ((cw[4 * x + b][e >> 2] >> (8 * (e & 3))) & 0xffu) << (8 * b);
+            tw[x] = wv;
+        }
+        uint8_t* dst = tile + (lc * EPL + e) * OST + rg * RPT;
+        if constexpr (RPT == 8) *reinterpret_cast<u32x2*>(dst) = u32x2{tw[0], tw[1]};
+        else *reinterpret_cast<u32x4*>(dst) = u32x4{tw[0], tw[1], tw[2], tw[3]};
+    }
+    __syncthreads();
+    // 128 transposed rows (k) x 8 chunks of 16 codes (n)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int kr = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
+        const int64_t kk = kb * 128 + kr, nn = nb * 128 + chunk * 16;
+        if (kk >= k || nn >= n) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + kr * OST + chunk * 16);
+        uint8_t* dst = qt + kk * ldqt + nn;
+        if (nn + 16 <= n) {
+            st_stream(dst, v);
+        } else {
+            const unsigned int wds[4] = {v.x, v.y, v.z, v.w};
+            for (int b = 0; b < 16 && nn + b < n; ++b) dst[b] = (uint8_t)(wds[b >> 2] >> (8 * (b & 3)));
+        }
+    }
+}
+
+// =============================================================================
 // 128x1: a workgroup takes 128 tokens x 128 channels.  Each thread loads TPT
 // consecutive tokens of one 16-byte channel granule, so after the column
 // max-abs (registers, then LDS across the token slices) it owns TPT
@@ -501,6 +597,20 @@ ds3_status launch_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_
         quant_w_128x128_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 2, q, ldq, s, nkb, pow2);
     else
         quant_w_128x128_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 4, q, ldq, s, nkb, pow2);
+    return launch_status();
+}
+
+ds3_status launch_quant_w_128x128_dual(const void* w, ds3_dtype wt, int64_t n, int64_t k, int64_t ldw, uint8_t* q,
+                                       int64_t ldq, float* s, uint8_t* qt, int64_t ldqt, float* s_t, int pow2,
+                                       hipStream_t st) {
+    const int64_t nkb = (k + 127) / 128, nnb = (n + 127) / 128;
+    dim3 grid((unsigned)nkb, (unsigned)nnb);
+    if (wt == DS3_BF16)
+        quant_w_128x128_dual_kernel<Bf16><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 2, q, ldq, s, qt, ldqt, s_t,
+                                                                 nkb, nnb, pow2);
+    else
+        quant_w_128x128_dual_kernel<F32><<<grid, 256, 0, st>>>((const uint8_t*)w, n, k, ldw * 4, q, ldq, s, qt, ldqt, s_t,
+                                                                nkb, nnb, pow2);
     return launch_status();
 }
 

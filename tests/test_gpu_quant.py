@@ -178,3 +178,18 @@ def test_swiglu_fused_with_quantizer(ds3, shape, pow2):
     assert np.mean(q == q_ref) > 0.98 and np.mean(s == s_ref) > 0.9
     deq, deq_ref = orc.dequant_rows(q, s), orc.dequant_rows(q_ref, s_ref)
     assert np.linalg.norm(deq - deq_ref) <= 2e-2 * np.linalg.norm(deq_ref)
+
+
+@pytest.mark.parametrize("pow2", [False, True])
+@pytest.mark.parametrize("bf16", [True, False])
+@pytest.mark.parametrize("shape", [(1024, 2048), (576, 1024), (130, 136), (5, 8), (300, 200)])
+def test_w_128x128_dual_layout(ds3, shape, bf16, pow2):
+    announce(f"dual weight quantizer {shape} bf16={bf16} pow2={pow2}")
+    w = wl.normal(shape, 0.02, 7)
+    if not bf16:
+        w = (w * np.float32(1.2345)).astype(np.float32)
+    fn = ds3.ds3_quant_w_128x128_dual_pow2 if pow2 else ds3.ds3_quant_w_128x128_dual
+    q, s, q_t, s_t = fn(dev(w, bf16=bf16))
+    q_ref, s_ref, qt_ref, st_ref = orc.quant_w_128x128_dual(w, pow2=pow2)
+    _cmp_codes_scales(q, s, q_ref, s_ref, "W")
+    _cmp_codes_scales(q_t, s_t, qt_ref, st_ref, "W^T")

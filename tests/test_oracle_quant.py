@@ -228,3 +228,22 @@ def test_swiglu_quant_is_the_composition_and_closed_forms():
     # power-of-two form: same activation, scales rounded up
     q2, s2 = orc.swiglu_quant_1x128(h, pow2=True)
     assert np.all(s2 >= s) and np.all(s2 < 2 * s.astype(np.float64))
+
+
+@pytest.mark.parametrize("pow2", [False, True])
+def test_dual_weight_quantization_is_a_transposition(pow2):
+    """Appendix B.2: block-wise (128x128) tiles only need transposing for the backward
+    pass.  The oracle quantizes W and W^T independently; codes and scales must be
+    transposes of each other, also with ragged edge blocks."""
+    w = wl.normal((200, 392), 0.02, 83)
+    w[5, 300] = 1.5
+    q, s, q_t, s_t = orc.quant_w_128x128_dual(w, pow2=pow2)
+    assert q.shape == (200, 392) and q_t.shape == (392, 200) and s.shape == (2, 4) and s_t.shape == (4, 2)
+    assert np.array_equal(q_t, q.T) and np.array_equal(s_t, s.T)
+    # and Dgrad through the transposed codes equals the exact product of the dequantized operands
+    dy = wl.normal((128, 200), 1.0, 84)[:, :128]
+    qa, sa = orc.quant_act_1x128(np.ascontiguousarray(dy))
+    wq = orc.dequant_blocks(q, s)[:128]                       # [128][392], rows = the contracted axis
+    ref = orc.dequant_rows(qa, sa) @ wq
+    got = orc.gemm_fp8_bs(qa, sa, q_t[:, :128], s_t[:, :1])
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-12)
