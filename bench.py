@@ -7,7 +7,7 @@ BF16): 1x128 quantization of X, 128x128 quantization of W and the block-scaled
 FP8 GEMM Y = X W^T in BF16.  Inputs are resident in HBM before the timed
 region starts.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5] [--pow2] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5|fused] [--pow2] [--no-cpu-baseline]
 
 The headline `value` is 2*M*N*K per step time (quantizers included) of the
 default workload; `kernels` lists every kernel of the step with its own
@@ -39,7 +39,7 @@ def parse():
                          "idle power state and its clocks have settled (the first ~15 ms after idle run 15-20%% slower)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket the kernels with HIP events on every n-th timed step only (1 = every step)")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "fused"])
     ap.add_argument("--unfused-swiglu", action="store_true", help="cfg3: separate SwiGLU and 1x128 quantizer kernels")
     ap.add_argument("--wgrad-from-cache", action="store_true",
                     help="cfg4: the Wgrad activation operand is re-tiled from the FP8 1x128 cache instead of re-quantized from BF16")

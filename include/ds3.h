@@ -299,6 +299,30 @@ ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inte
                                        float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
 
 /*
+ * RMSNorm fused with the 1x128 quantization of its output, the input of the
+ * Linear that follows the normalisation (Section 3.3: normalisation operators
+ * keep their original precision; Section 3.5.2 asks for the FP8 cast to be fused
+ * with its producer instead of a round trip through HBM).  Per row
+ *     r = 1 / sqrt(mean_c(x[c]^2) + eps)          (FP32; x is BF16)
+ *     a[c] = bf16(x[c] * r * gamma[c])            (round to nearest even)
+ * and then exactly ds3_quant_act_1x128 (or its _pow2 form) applied to a.
+ *   x      [rows][ldx] BF16, `cols` valid columns, cols <= 8192
+ *   gamma  [cols] FP32, DEVICE
+ *   y      [rows][ldy] BF16 or NULL: if given, a is also written there
+ *   q, s   as in ds3_quant_act_1x128
+ * cols % 8 == 0; x, y, q, gamma 16-byte aligned; ldx, ldy % 8 == 0; ldq % 16 == 0;
+ * eps >= 0.  The order of the FP32 additions of the squares is unspecified.
+ */
+ds3_status ds3_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx,
+                                   const float* gamma, float eps, void* y, int64_t ldy,
+                                   uint8_t* q, int64_t ldq,
+                                   float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+ds3_status ds3_rmsnorm_quant_1x128_pow2(const void* x, int64_t rows, int64_t cols, int64_t ldx,
+                                        const float* gamma, float eps, void* y, int64_t ldy,
+                                        uint8_t* q, int64_t ldq,
+                                        float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+
+/*
  * Machine probes for the benchmark (they compute nothing of the method; they
  * exist so that a roofline fraction can be read against what this chip
  * sustains, not only against the published peak).

@@ -270,3 +270,19 @@ def quant_w_128x128_dual(w, pow2: bool = False):
     q, s = quant_w_128x128(w, pow2=pow2)
     q_t, s_t = quant_w_128x128(np.ascontiguousarray(w.T), pow2=pow2)
     return q, s, q_t, s_t
+
+
+def rmsnorm(x, gamma, eps: float) -> np.ndarray:
+    """RMSNorm (the normalisation DeepSeek-V3 applies before attention and FFN,
+    Section 2 / Figure 2; Section 3.3 keeps it in its original precision):
+    x[c] / sqrt(mean_c x[c]^2 + eps) * gamma[c], float64.  eps is the caller's
+    (the report does not print it)."""
+    x = np.asarray(x).astype(np.float64)
+    g = np.asarray(gamma).astype(np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + float(eps)) * g[None, :]
+
+
+def rmsnorm_quant_1x128(x, gamma, eps: float, pow2: bool = False):
+    """RMSNorm output as the following Linear receives it: a BF16 tensor
+    (reading), quantized per 1x128 tile.  The composition a fused kernel must equal."""
+    return quant_act_1x128(round_to_bf16(rmsnorm(x, gamma, eps)), pow2=pow2)

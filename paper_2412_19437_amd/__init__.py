@@ -30,6 +30,7 @@ SYMBOLS = [
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
     "ds3_retile_1x128_to_128x1", "ds3_retile_1x128_to_128x1_pow2",
     "ds3_quant_w_128x128_dual", "ds3_quant_w_128x128_dual_pow2",
+    "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2",
 ]
 
 
@@ -65,6 +66,9 @@ def _load() -> ctypes.CDLL:
     lib.ds3_retile_1x128_to_128x1_pow2.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_quant_w_128x128_dual.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i64, vp, vp]
     lib.ds3_quant_w_128x128_dual_pow2.argtypes = [vp, i32, i64, i64, i64, vp, i64, vp, vp, i64, vp, vp]
+    f32 = ctypes.c_float
+    lib.ds3_rmsnorm_quant_1x128.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_rmsnorm_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
@@ -286,6 +290,30 @@ def ds3_quant_w_128x128_dual(w: torch.Tensor):
 def ds3_quant_w_128x128_dual_pow2(w: torch.Tensor):
     """As ds3_quant_w_128x128_dual with power-of-two scales."""
     return _quant_w_dual("ds3_quant_w_128x128_dual_pow2", w)
+
+
+def _rmsnorm_quant(entry: str, x, gamma, eps, want_y, k_major_scales):
+    rows, cols, ldx = _rows2d(x, "x")
+    if x.dtype != torch.bfloat16 or gamma.dtype != torch.float32 or gamma.numel() != cols or not gamma.is_contiguous():
+        raise TypeError("x must be BF16 and gamma a contiguous FP32 vector of x's width")
+    q = _codes(rows, cols, x.device)
+    s = _scales(rows, (cols + 127) // 128, x.device, k_major_scales)
+    y = torch.empty((rows, cols), dtype=torch.bfloat16, device=x.device) if want_y else None
+    st = getattr(_L(), entry)(x.data_ptr(), rows, cols, ldx, gamma.data_ptr(), float(eps),
+                              y.data_ptr() if want_y else None, cols, q.data_ptr(), (cols + 15) // 16 * 16,
+                              s.data_ptr(), s.stride(0), s.stride(1), _stream())
+    _check(st, entry)
+    return (q, s, y) if want_y else (q, s)
+
+
+def ds3_rmsnorm_quant_1x128(x, gamma, eps: float = 1e-6, want_y: bool = False, k_major_scales: bool = True):
+    """RMSNorm(x) * gamma rounded to BF16, 1x128-quantized: (codes, scales[, the BF16 activation])."""
+    return _rmsnorm_quant("ds3_rmsnorm_quant_1x128", x, gamma, eps, want_y, k_major_scales)
+
+
+def ds3_rmsnorm_quant_1x128_pow2(x, gamma, eps: float = 1e-6, want_y: bool = False, k_major_scales: bool = True):
+    """As ds3_rmsnorm_quant_1x128 with power-of-two scales."""
+    return _rmsnorm_quant("ds3_rmsnorm_quant_1x128_pow2", x, gamma, eps, want_y, k_major_scales)
 
 
 def _swiglu_quant(entry: str, h: torch.Tensor, k_major_scales: bool):

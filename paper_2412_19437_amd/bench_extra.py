@@ -44,7 +44,7 @@ def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=Fal
           dual_weight_quant=False):
     global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT
     _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT = unfused_swiglu, wgrad_from_cache, dual_weight_quant
-    step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5}[workload](
+    step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5, "fused": _fused}[workload](
         _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
     if pow2:
         cfg["workload"] += "; power-of-two scaling factors, scales applied by the matrix instruction"
@@ -228,3 +228,37 @@ def _cfg5(ds3, torch, wl, dev, variant):
                        "kv_b 512->32768; quant 1x128 + quant 128x128 + block-scaled FP8 GEMM each, BF16 out",
            "gemm_variant": variant}
     return step, kernels, flops, cfg, "gemm_fp8_bs(q_b 8192x24576x1536)"
+
+
+def _fused(ds3, torch, wl, dev, variant):
+    """The producer-fused and layout kernels around the Linear at the dense-layer shapes (4096 tokens):
+    RMSNorm -> quant, SwiGLU -> quant, FP8 cache re-tiling, dual-layout weight quantizer.  All HBM-bound;
+    there is no GEMM in this workload, so `value` counts no flops."""
+    Timed = _timed()
+    T, H, I = 4096, wl.HIDDEN, wl.DENSE_INTER
+    x = _bf16(torch, wl.cfg2_x(), dev)
+    gen = torch.Generator(device=dev).manual_seed(wl.seed_for(6, 0))
+    gamma = 1.0 + 0.1 * torch.randn(H, generator=gen, device=dev)
+    h = (torch.randn((T, 2 * I), generator=gen, device=dev) * 2.0).to(torch.bfloat16)
+    w = _bf16(torch, wl.cfg2_w(), dev)
+    dy = _bf16(torch, wl.cfg4_dy(), dev)
+    qdy, sdy = ds3.ds3_quant_act_1x128(dy)
+    groups = lambda r, c: r * ((c + 127) // 128)
+    kernels = [
+        Timed("rmsnorm_quant_1x128(X 4096x7168)", lambda: ds3.ds3_rmsnorm_quant_1x128(x, gamma, 1e-6), "GB/s",
+              (T * H * 3 + groups(T, H) * 4 + H * 4) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("swiglu_quant_1x128(h 4096x36864)", lambda: ds3.ds3_swiglu_quant_1x128(h), "GB/s",
+              (T * I * 5 + groups(T, I) * 4) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("retile_1x128_to_128x1(dY 4096x18432)", lambda: ds3.ds3_retile_1x128_to_128x1(qdy, sdy), "GB/s",
+              (T * I * 2 + 2 * groups(T, I) * 4) / 1e9, "hbm", PEAK_HBM_GBS),
+        Timed("quant_w_128x128_dual(W 18432x7168)", lambda: ds3.ds3_quant_w_128x128_dual(w), "GB/s",
+              (I * H * 4 + 2 * (I * H // 16384) * 4) / 1e9, "hbm", PEAK_HBM_GBS),
+    ]
+
+    def step(record):
+        for k in kernels:
+            k(record)
+
+    cfg = {"workload": "fused: producer-fused quantizers and layout kernels at the dense-layer shapes, 4096 tokens "
+                       "(RMSNorm->1x128, SwiGLU->1x128, 1x128 cache -> 128x1, W -> codes of W and W^T)"}
+    return step, kernels, 0.0, cfg, "quant_w_128x128_dual(W 18432x7168)"

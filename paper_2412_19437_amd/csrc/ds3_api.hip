@@ -240,6 +240,33 @@ ds3_status ds3_retile_1x128_to_128x1_pow2(const uint8_t* q, int64_t rows, int64_
     return retile(1, q, rows, cols, ldq, s, s_stride_row, s_stride_kb, q_t, ldqt, s_t, st_stride_col, st_stride_tb, stream);
 }
 
+static ds3_status rmsnorm_quant(int pow2, const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma,
+                                float eps, void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s, int64_t ssr,
+                                int64_t ssk, void* stream) {
+    if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return DS3_OK;
+    if (!x || !gamma || !q || !s) return DS3_ERR_NULL;
+    if (ldx < cols || ldq < cols || (y && ldy < cols)) return DS3_ERR_SHAPE;
+    if (!(eps >= 0.0f)) return DS3_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(q) || !aligned16(gamma) || (y && !aligned16(y)) || cols % 8 || ldx % 8 || ldq % 16 ||
+        (y && ldy % 8))
+        return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || cols > 8192) return DS3_ERR_UNSUPPORTED;
+    return launch_rmsnorm_quant_1x128(x, rows, cols, ldx, gamma, eps, y, ldy, q, ldq, s, ssr, ssk, pow2,
+                                      static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma, float eps,
+                                   void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s, int64_t s_stride_row,
+                                   int64_t s_stride_kb, void* stream) {
+    return rmsnorm_quant(0, x, rows, cols, ldx, gamma, eps, y, ldy, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+ds3_status ds3_rmsnorm_quant_1x128_pow2(const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma,
+                                        float eps, void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s,
+                                        int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return rmsnorm_quant(1, x, rows, cols, ldx, gamma, eps, y, ldy, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+
 static ds3_status swiglu_quant(int pow2, const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
                                float* s, int64_t ssr, int64_t ssk, void* stream) {
     if (rows < 0 || inter < 0) return DS3_ERR_SHAPE;

@@ -22,6 +22,9 @@ ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh
 ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s,
                                         int64_t ssr, int64_t ssk, uint8_t* qt, int64_t ldqt, float* s_t, int64_t ssc,
                                         int64_t sst, int pow2, hipStream_t st);
+ds3_status launch_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma, float eps,
+                                      void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s, int64_t ssr, int64_t ssk,
+                                      int pow2, hipStream_t st);
 ds3_status launch_swiglu_quant_1x128(const void* h, int64_t rows, int64_t inter, int64_t ldh, uint8_t* q, int64_t ldq,
                                      float* s, int64_t ssr, int64_t ssk, int pow2, hipStream_t st);
 ds3_status launch_probe_mfma(int iters, float* out, int blocks, hipStream_t st);

@@ -21,6 +21,16 @@ __device__ __forceinline__ void st_stream(uint8_t* p, V v) {
     *reinterpret_cast<V*>(p) = v;
 }
 
+// Byte offset inside a [128 rows][128 + 16 bytes] LDS tile whose 16-byte chunks are
+// XOR-swizzled by a key taken from the row index (bits KS .. KS+2): the lanes of a
+// wave that write the same chunk position of rows 2^KS apart then hit different banks
+// (the row stride of 144 bytes alone repeats the bank every 16 rows).  `off` is the
+// byte offset inside the row; accesses never straddle a 16-byte chunk.
+template <int KS>
+__device__ __forceinline__ int tile_off(int row, int off) {
+    return row * 144 + ((((off >> 4) ^ (row >> KS)) & 7) << 4) + (off & 15);
+}
+
 // ----- element traits: how many elements one 16-byte load carries --------------
 struct Bf16 { static constexpr int EPL = 8; };   // elements per 128-bit load
 struct F32  { static constexpr int EPL = 4; };
@@ -188,6 +198,7 @@ __global__ __launch_bounds__(256) void quant_w_128x128_dual_kernel(
     constexpr int NRG = 256 / LPR;                // row groups
     constexpr int RPT = 128 / NRG;                // consecutive rows per thread (8 BF16, 16 FP32)
     constexpr int OST = 128 + 16;
+    constexpr int KS = EPL == 8 ? 3 : 4;          // swizzle key: the lane index across the block row
     __shared__ unsigned int red[16];
     __shared__ __attribute__((aligned(16))) uint8_t tile[128 * OST];   // [k][n]
     const int64_t kb = blockIdx.x, nb = blockIdx.y;
@@ -243,7 +254,7 @@ __global__ __launch_bounds__(256) void quant_w_128x128_dual_kernel(
             for (int b = 0; b < 4; ++b) wv |= ((cw[4 * x + b][e >> 2] >> (8 * (e & 3))) & 0xffu) << (8 * b);
             tw[x] = wv;
         }
-        uint8_t* dst = tile + (lc * EPL + e) * OST + rg * RPT;
+        uint8_t* dst = tile + tile_off<KS>(lc * EPL + e, rg * RPT);
         if constexpr (RPT == 8) *reinterpret_cast<u32x2*>(dst) = u32x2{tw[0], tw[1]};
         else *reinterpret_cast<u32x4*>(dst) = u32x4{tw[0], tw[1], tw[2], tw[3]};
     }
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(256) void quant_w_128x128_dual_kernel(
         const int kr = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
         const int64_t kk = kb * 128 + kr, nn = nb * 128 + chunk * 16;
         if (kk >= k || nn >= n) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + kr * OST + chunk * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + tile_off<KS>(kr, chunk * 16));
         uint8_t* dst = qt + kk * ldqt + nn;
         if (nn + 16 <= n) {
             st_stream(dst, v);
@@ -282,6 +293,7 @@ __global__ __launch_bounds__(256, (T::EPL == 8 ? 7 : 4)) void quant_act_128x1_ke
     constexpr int NSL = 256 / LPR;                // token slices (16 for BF16, 8 for FP32)
     constexpr int TPT = 128 / NSL;                // consecutive tokens per thread (8 / 16)
     constexpr int OST = 128 + 16;                 // LDS row stride of the [channel][token] tile
+    constexpr int KS = EPL == 8 ? 3 : 4;          // swizzle key: the lane index across the channels
     // the per-slice maxima are dead once the multipliers are known: they share the code tile's memory
     __shared__ __attribute__((aligned(16))) uint8_t tile[128 * OST];
     __shared__ float rmul[128];
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(256, (T::EPL == 8 ? 7 : 4)) void quant_act_128x1_ke
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
         const float r = rmul[lc * EPL + i];
-        uint8_t* dst = tile + (lc * EPL + i) * OST + sl * TPT;
+        uint8_t* dst = tile + tile_off<KS>(lc * EPL + i, sl * TPT);
 #pragma unroll
         for (int p = 0; p < TPT; p += 8) {
             float y[8];
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(256, (T::EPL == 8 ? 7 : 4)) void quant_act_128x1_ke
         const int ch = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
         const int64_t tok = t0 + chunk * 16;
         if (c0 + ch >= cols || tok >= rows) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + ch * OST + chunk * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + tile_off<KS>(ch, chunk * 16));
         uint8_t* dst = qt + (c0 + ch) * ldq + tok;
         if (tok + 16 <= rows) {
             st_stream(dst, v);
@@ -470,7 +482,7 @@ __global__ __launch_bounds__(256) void retile_1x128_to_128x1_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float r = rmul[lc * 16 + w * 4 + i];
-            *reinterpret_cast<unsigned int*>(tile + (lc * 16 + w * 4 + i) * OST + sl * TPT) =
+            *reinterpret_cast<unsigned int*>(tile + tile_off<4>(lc * 16 + w * 4 + i, sl * TPT)) =
                 cvt4_e4m3(y[0][i] * r, y[1][i] * r, y[2][i] * r, y[3][i] * r);
         }
     }
@@ -480,7 +492,7 @@ __global__ __launch_bounds__(256) void retile_1x128_to_128x1_kernel(
         const int ch = it * 32 + (threadIdx.x >> 3), chunk = threadIdx.x & 7;
         const int64_t tok = t0 + chunk * 16;
         if (c0 + ch >= cols || tok >= rows) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + ch * OST + chunk * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(tile + tile_off<4>(ch, chunk * 16));
         uint8_t* dst = qt + (c0 + ch) * ldqt + tok;
         if (tok + 16 <= rows) {
             st_stream(dst, v);
@@ -540,6 +552,84 @@ __global__ __launch_bounds__(256) void swiglu_quant_1x128_kernel(
             const int64_t col = (kb0 + t) * 128 + lane16 * 8;
             u32x2 c = {cvt4_e4m3(v[0], v[1], v[2], v[3]), cvt4_e4m3(v[4], v[5], v[6], v[7])};
             st_stream(q + row * ldq + col, c);
+        }
+    }
+}
+
+// =============================================================================
+// RMSNorm fused with the 1x128 quantizer of the following Linear's input: one
+// workgroup per row.  The row (at most 8192 BF16 elements) stays in registers
+// between the sum of squares and the cast; each of the 16 DPP rows of the
+// workgroup then handles every sixteenth 1x128 tile exactly as the stand-alone
+// quantizer does.  The normalised activation is rounded to BF16 first (it is a
+// BF16 tensor for every other consumer) and optionally written out.
+// =============================================================================
+constexpr int kNormMaxGranules = 4;               // 16-byte granules per lane: rows of up to 4 * 2048 elements
+
+__global__ __launch_bounds__(256) void rmsnorm_quant_1x128_kernel(
+    const uint8_t* __restrict__ x, int64_t cols, int64_t ldx_bytes, const float* __restrict__ gamma,
+    float eps, uint8_t* __restrict__ y, int64_t ldy_bytes, uint8_t* __restrict__ q, int64_t ldq,
+    float* __restrict__ s, int64_t ssr, int64_t ssk, int pow2) {
+    __shared__ float red[4];
+    const int lane16 = threadIdx.x & 15, t16 = threadIdx.x >> 4;
+    const int64_t row = blockIdx.x;
+    const uint8_t* xr = x + row * ldx_bytes;
+
+    // granule i of this lane: tile 16*i + t16, elements [lane16*8, +8) of it
+    u32x4 g[kNormMaxGranules];
+    f32x4 gm[kNormMaxGranules][2];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kNormMaxGranules; ++i) {
+        const int64_t col = ((int64_t)(16 * i + t16) << 7) + lane16 * 8;
+        g[i] = u32x4{0u, 0u, 0u, 0u};
+        gm[i][0] = gm[i][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (col < cols) {
+            g[i] = ld_stream(xr + col * 2);
+            gm[i][0] = *reinterpret_cast<const f32x4*>(gamma + col);
+            gm[i][1] = *reinterpret_cast<const f32x4*>(gamma + col + 4);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kNormMaxGranules; ++i) {
+        float v[8];
+        widen<Bf16>(g[i], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(v[e], v[e], ss);
+    }
+    // sum over the workgroup: butterflies inside the 16-lane rows, across the wave's four rows, then LDS
+    ss += as_f32(dpp_u32<0xB1>(as_u32(ss)));
+    ss += as_f32(dpp_u32<0x4E>(as_u32(ss)));
+    ss += as_f32(dpp_u32<0x141>(as_u32(ss)));
+    ss += as_f32(dpp_u32<0x140>(as_u32(ss)));
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = (red[0] + red[1]) + (red[2] + red[3]);
+    const float rstd = 1.0f / sqrtf(ss / (float)cols + eps);
+
+#pragma unroll
+    for (int i = 0; i < kNormMaxGranules; ++i) {
+        const int64_t kb = 16 * i + t16;
+        const int64_t col = (kb << 7) + lane16 * 8;
+        if ((kb << 7) < cols) {                   // a whole DPP row decides together
+            const bool ok = col < cols;
+            float v[8];
+            widen<Bf16>(g[i], v);
+            const float gmv[8] = {gm[i][0].x, gm[i][0].y, gm[i][0].z, gm[i][0].w, gm[i][1].x, gm[i][1].y, gm[i][1].z, gm[i][1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] * rstd * gmv[e];
+            const u32x4 w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+            if (y != nullptr && ok) st_stream(y + row * ldy_bytes + col * 2, w);
+            const unsigned int m = row16_max_bits(granule_amax_bits<Bf16>(w));
+            const GroupScale gs = group_scale(as_f32(m), pow2);
+            if (lane16 == 0) s[row * ssr + kb * ssk] = gs.s;
+            float r[8];
+            widen<Bf16>(w, r);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = r[e] * gs.r;
+            if (ok) st_stream(q + row * ldq + col, u32x2{cvt4_e4m3(r[0], r[1], r[2], r[3]), cvt4_e4m3(r[4], r[5], r[6], r[7])});
         }
     }
 }
@@ -637,6 +727,15 @@ ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t 
                                         int64_t sst, int pow2, hipStream_t st) {
     dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
     retile_1x128_to_128x1_kernel<<<grid, 256, 0, st>>>(q, rows, cols, ldq, s, ssr, ssk, qt, ldqt, s_t, ssc, sst, pow2);
+    return launch_status();
+}
+
+ds3_status launch_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma, float eps,
+                                      void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s, int64_t ssr, int64_t ssk,
+                                      int pow2, hipStream_t st) {
+    if (cols > (int64_t)kNormMaxGranules * 2048) return DS3_ERR_UNSUPPORTED;
+    rmsnorm_quant_1x128_kernel<<<dim3((unsigned)rows), 256, 0, st>>>(
+        (const uint8_t*)x, cols, ldx * 2, gamma, eps, (uint8_t*)y, ldy * 2, q, ldq, s, ssr, ssk, pow2);
     return launch_status();
 }
 

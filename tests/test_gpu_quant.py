@@ -193,3 +193,26 @@ def test_w_128x128_dual_layout(ds3, shape, bf16, pow2):
     q_ref, s_ref, qt_ref, st_ref = orc.quant_w_128x128_dual(w, pow2=pow2)
     _cmp_codes_scales(q, s, q_ref, s_ref, "W")
     _cmp_codes_scales(q_t, s_t, qt_ref, st_ref, "W^T")
+
+
+@pytest.mark.parametrize("pow2", [False, True])
+@pytest.mark.parametrize("shape", [(512, 7168), (33, 1536), (5, 512), (3, 200), (1, 8), (9, 8192)])
+def test_rmsnorm_fused_with_quantizer(ds3, shape, pow2):
+    """The BF16 activation the kernel writes is within one BF16 ulp of the FP64 RMSNorm
+    (FP32 sum of squares, FP32 products); its codes and scales must equal, bit for bit,
+    the oracle's 1x128 quantization of that same BF16 activation."""
+    announce(f"rmsnorm+quant {shape} pow2={pow2}")
+    rng = np.random.default_rng(8)
+    x = wl.cfg2_x(m=shape[0], k=shape[1])
+    gamma = (1.0 + 0.1 * rng.standard_normal(shape[1])).astype(np.float32)
+    fn = ds3.ds3_rmsnorm_quant_1x128_pow2 if pow2 else ds3.ds3_rmsnorm_quant_1x128
+    q, s, y = fn(dev(x, bf16=True), dev(gamma), 1e-6, want_y=True)
+    y = host(y)
+    ref = orc.rmsnorm(x, gamma, 1e-6)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -120))) - 7)
+    assert np.all(np.abs(y - ref) <= ulp)
+    assert np.mean(np.abs(y - ref) <= 0.5 * ulp * 1.001) > 0.99
+    _cmp_codes_scales(q, s, *orc.quant_act_1x128(y, pow2=pow2), "fused vs quant(rmsnorm)")
+    # without the BF16 output the codes are the same
+    q2, s2 = fn(dev(x, bf16=True), dev(gamma), 1e-6)
+    assert torch.equal(q2, q) and torch.equal(s2, s)

@@ -247,3 +247,28 @@ def test_dual_weight_quantization_is_a_transposition(pow2):
     ref = orc.dequant_rows(qa, sa) @ wq
     got = orc.gemm_fp8_bs(qa, sa, q_t[:, :128], s_t[:, :1])
     assert np.allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_rmsnorm_closed_forms_library_and_composition():
+    import torch
+    rng = np.random.default_rng(85)
+    x = wl.cfg2_x(m=6, k=512)
+    gamma = (1.0 + 0.1 * rng.standard_normal(512)).astype(np.float32)
+    y = orc.rmsnorm(x, gamma, 1e-6)
+    # library third opinion
+    lib = torch.nn.functional.rms_norm(torch.from_numpy(x).double(), (512,), torch.from_numpy(gamma).double(), 1e-6).numpy()
+    assert np.allclose(y, lib, rtol=1e-12, atol=1e-14)
+    # with unit gain and no eps every row has unit mean square; scaling the input changes nothing
+    y1 = orc.rmsnorm(x, np.ones(512, np.float32), 0.0)
+    assert np.allclose(np.mean(y1 * y1, axis=1), 1.0, rtol=1e-12)
+    assert np.allclose(orc.rmsnorm(3.5 * x.astype(np.float64), np.ones(512), 0.0), y1, rtol=1e-12)
+    # a constant row normalises to +-gamma
+    c = np.full((1, 512), -2.5, np.float32)
+    assert np.allclose(orc.rmsnorm(c, gamma, 0.0), -gamma[None, :].astype(np.float64), rtol=1e-12)
+    # eps dominates a zero row: output zero, quantized as an all-zero tile
+    q0, s0 = orc.rmsnorm_quant_1x128(np.zeros((1, 512), np.float32), gamma, 1e-6)
+    assert np.all(s0 == 1.0) and np.all(q0 == 0)
+    # the fused definition is the composition of its parts
+    q, s = orc.rmsnorm_quant_1x128(x, gamma, 1e-6)
+    q2, s2 = orc.quant_act_1x128(orc.round_to_bf16(y))
+    assert np.array_equal(q, q2) and np.array_equal(s, s2)
