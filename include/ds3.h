@@ -323,6 +323,25 @@ ds3_status ds3_rmsnorm_quant_1x128_pow2(const void* x, int64_t rows, int64_t col
                                         float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
 
 /*
+ * AdamW step with low-precision optimizer states (Section 3.3.3: the first and
+ * second moments are kept in BF16, master weights and gradients in FP32;
+ * Section 4.2 gives beta1 = 0.9, beta2 = 0.95, weight_decay = 0.1).  For every
+ * parameter, in FP32:
+ *     m   = beta1 * m + (1 - beta1) * g            v = beta2 * v + (1 - beta2) * g * g
+ *     w   = w - lr * ( (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps) + weight_decay * w )
+ * and m, v are rounded to BF16 (nearest even) when stored; the update uses the
+ * unrounded values.  The two bias corrections are formed in double on the host.
+ *   master_w [n] FP32 in/out, grad [n] FP32, m, v [n] BF16 in/out,
+ *   w_bf16   [n] BF16 out or NULL: the BF16 copy of the new weights the next
+ *            forward pass quantizes from.   step = t >= 1.
+ * n % 8 == 0, all pointers DEVICE and 16-byte aligned.  22 bytes of HBM traffic
+ * per parameter (24 with FP32 moments, which would also need 8 more bytes resident).
+ */
+ds3_status ds3_adamw_bf16_states(int64_t n, float* master_w, const float* grad, void* m, void* v, void* w_bf16,
+                                 float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                                 void* stream);
+
+/*
  * Machine probes for the benchmark (they compute nothing of the method; they
  * exist so that a roofline fraction can be read against what this chip
  * sustains, not only against the published peak).

@@ -286,3 +286,25 @@ def rmsnorm_quant_1x128(x, gamma, eps: float, pow2: bool = False):
     """RMSNorm output as the following Linear receives it: a BF16 tensor
     (reading), quantized per 1x128 tile.  The composition a fused kernel must equal."""
     return quant_act_1x128(round_to_bf16(rmsnorm(x, gamma, eps)), pow2=pow2)
+
+
+def adamw_step(w, g, m, v, lr, beta1, beta2, eps, weight_decay, step, bf16_moments: bool = True):
+    """One AdamW step (decoupled weight decay, bias-corrected moments) in float64,
+    with the storage formats of Section 3.3.3: the moments are BF16 tensors (they
+    arrive as BF16 values and are rounded to BF16 when stored), the master weights
+    FP32.  The update uses the moments before their storage rounding (reading).
+    Returns (w_new float32, m_new, v_new as float32 arrays holding the stored
+    values, w_bf16 float32 array holding the BF16 copy).  With
+    ``bf16_moments=False`` nothing is rounded and everything is returned in float64:
+    the textbook algorithm, against which the function is pinned."""
+    w = np.asarray(w).astype(np.float64)
+    g = np.asarray(g).astype(np.float64)
+    m = beta1 * np.asarray(m).astype(np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v).astype(np.float64) + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    w = w - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * w)
+    if not bf16_moments:
+        return w, m, v, w
+    w32 = w.astype(np.float32)
+    return w32, round_to_bf16(m), round_to_bf16(v), round_to_bf16(w32)

@@ -30,7 +30,7 @@ SYMBOLS = [
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
     "ds3_retile_1x128_to_128x1", "ds3_retile_1x128_to_128x1_pow2",
     "ds3_quant_w_128x128_dual", "ds3_quant_w_128x128_dual_pow2",
-    "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2",
+    "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2", "ds3_adamw_bf16_states",
 ]
 
 
@@ -69,6 +69,7 @@ def _load() -> ctypes.CDLL:
     f32 = ctypes.c_float
     lib.ds3_rmsnorm_quant_1x128.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_rmsnorm_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_adamw_bf16_states.argtypes = [i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
     lib.ds3_gemm_num_variants.argtypes = []
@@ -314,6 +315,23 @@ def ds3_rmsnorm_quant_1x128(x, gamma, eps: float = 1e-6, want_y: bool = False, k
 def ds3_rmsnorm_quant_1x128_pow2(x, gamma, eps: float = 1e-6, want_y: bool = False, k_major_scales: bool = True):
     """As ds3_rmsnorm_quant_1x128 with power-of-two scales."""
     return _rmsnorm_quant("ds3_rmsnorm_quant_1x128_pow2", x, gamma, eps, want_y, k_major_scales)
+
+
+def ds3_adamw_bf16_states(master_w, grad, m, v, lr, beta1, beta2, eps, weight_decay, step, w_bf16=None):
+    """One AdamW step in place: master_w FP32, grad FP32, m and v BF16 (all flat, same length, contiguous);
+    w_bf16 (optional, BF16) receives the rounded new weights."""
+    n = master_w.numel()
+    ok = (master_w.dtype == torch.float32 and grad.dtype == torch.float32 and m.dtype == torch.bfloat16
+          and v.dtype == torch.bfloat16 and grad.numel() == n and m.numel() == n and v.numel() == n)
+    ok = ok and all(t.is_contiguous() for t in (master_w, grad, m, v))
+    if w_bf16 is not None:
+        ok = ok and w_bf16.dtype == torch.bfloat16 and w_bf16.numel() == n and w_bf16.is_contiguous()
+    if not ok:
+        raise TypeError("master_w, grad: FP32; m, v[, w_bf16]: BF16; all contiguous and of one length")
+    st = _L().ds3_adamw_bf16_states(n, master_w.data_ptr(), grad.data_ptr(), m.data_ptr(), v.data_ptr(),
+                                    w_bf16.data_ptr() if w_bf16 is not None else None, float(lr), float(beta1),
+                                    float(beta2), float(eps), float(weight_decay), int(step), _stream())
+    _check(st, "ds3_adamw_bf16_states")
 
 
 def _swiglu_quant(entry: str, h: torch.Tensor, k_major_scales: bool):

@@ -259,6 +259,22 @@ def _fused(ds3, torch, wl, dev, variant):
         for k in kernels:
             k(record)
 
+    # AdamW with BF16 moments on the layer's 132 M parameters: 22 bytes of traffic per parameter
+    nparam = I * H
+    mw = torch.randn(nparam, generator=gen, device=dev) * 0.02
+    gr = torch.randn(nparam, generator=gen, device=dev) * 1e-3
+    m1 = torch.zeros(nparam, dtype=torch.bfloat16, device=dev)
+    v1 = torch.zeros(nparam, dtype=torch.bfloat16, device=dev)
+    wb = torch.empty(nparam, dtype=torch.bfloat16, device=dev)
+    state = {"t": 0}
+
+    def adamw():
+        state["t"] += 1
+        ds3.ds3_adamw_bf16_states(mw, gr, m1, v1, 2.2e-4, 0.9, 0.95, 1e-8, 0.1, state["t"], w_bf16=wb)
+
+    kernels.append(Timed("adamw_bf16_states(132M parameters)", adamw, "GB/s", nparam * 22 / 1e9, "hbm", PEAK_HBM_GBS))
+
     cfg = {"workload": "fused: producer-fused quantizers and layout kernels at the dense-layer shapes, 4096 tokens "
-                       "(RMSNorm->1x128, SwiGLU->1x128, 1x128 cache -> 128x1, W -> codes of W and W^T)"}
+                       "(RMSNorm->1x128, SwiGLU->1x128, 1x128 cache -> 128x1, W -> codes of W and W^T), and the AdamW step with "
+                       "BF16 moments on the layer's parameters"}
     return step, kernels, 0.0, cfg, "quant_w_128x128_dual(W 18432x7168)"

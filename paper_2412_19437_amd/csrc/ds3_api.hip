@@ -1,5 +1,7 @@
 // The C ABI of libds3: argument checking on the host, then a kernel launch.
 // No entry point allocates, synchronises or touches device data on the host.
+#include <cmath>
+
 #include "ds3_internal.h"
 
 namespace ds3 { int gemm_num_variants(); }
@@ -238,6 +240,22 @@ ds3_status ds3_retile_1x128_to_128x1_pow2(const uint8_t* q, int64_t rows, int64_
                                           int64_t s_stride_row, int64_t s_stride_kb, uint8_t* q_t, int64_t ldqt,
                                           float* s_t, int64_t st_stride_col, int64_t st_stride_tb, void* stream) {
     return retile(1, q, rows, cols, ldq, s, s_stride_row, s_stride_kb, q_t, ldqt, s_t, st_stride_col, st_stride_tb, stream);
+}
+
+ds3_status ds3_adamw_bf16_states(int64_t n, float* master_w, const float* grad, void* m, void* v, void* w_bf16, float lr,
+                                 float beta1, float beta2, float eps, float weight_decay, int64_t step, void* stream) {
+    if (n < 0 || step < 1) return DS3_ERR_SHAPE;
+    if (n == 0) return DS3_OK;
+    if (!master_w || !grad || !m || !v) return DS3_ERR_NULL;
+    if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps >= 0.f)) return DS3_ERR_SHAPE;
+    if (n % 8 || !aligned16(master_w) || !aligned16(grad) || !aligned16(m) || !aligned16(v) || (w_bf16 && !aligned16(w_bf16)))
+        return DS3_ERR_ALIGN;
+    if (n / 8 > kMaxDim * 256ll) return DS3_ERR_UNSUPPORTED;
+    // bias corrections in double on the host, handed over as FP32 reciprocals
+    const float rbc1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)step)));
+    const float rbc2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)step)));
+    return launch_adamw_bf16_states(n, master_w, grad, m, v, w_bf16, lr, beta1, beta2, eps, weight_decay, rbc1, rbc2,
+                                    static_cast<hipStream_t>(stream));
 }
 
 static ds3_status rmsnorm_quant(int pow2, const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma,

@@ -634,6 +634,46 @@ __global__ __launch_bounds__(256) void rmsnorm_quant_1x128_kernel(
     }
 }
 
+// =============================================================================
+// AdamW step with BF16 first and second moments, FP32 master weights and FP32
+// gradients (Section 3.3.3, Low-Precision Optimizer States).  One pass over the
+// parameters: 8 per thread, 16-byte accesses.  The moments are updated in FP32
+// from their BF16 values and rounded back to BF16 (nearest even) for storage;
+// the update itself uses the unrounded FP32 moments.
+// =============================================================================
+struct AdamwArgs { float lr, beta1, beta2, eps, wd, rbc1, rbc2; };   // rbc = 1 / (1 - beta^t)
+
+__global__ __launch_bounds__(256) void adamw_bf16_states_kernel(int64_t n8, float* __restrict__ w, const float* __restrict__ g,
+                                                                uint8_t* __restrict__ m, uint8_t* __restrict__ v,
+                                                                uint8_t* __restrict__ wb, AdamwArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n8) return;
+    const u32x4 g0 = ld_stream(reinterpret_cast<const uint8_t*>(g) + i * 32);
+    const u32x4 g1 = ld_stream(reinterpret_cast<const uint8_t*>(g) + i * 32 + 16);
+    const u32x4 w0 = ld_stream(reinterpret_cast<const uint8_t*>(w) + i * 32);
+    const u32x4 w1 = ld_stream(reinterpret_cast<const uint8_t*>(w) + i * 32 + 16);
+    const u32x4 mm = ld_stream(m + i * 16);
+    const u32x4 vv = ld_stream(v + i * 16);
+    float gf[8] = {as_f32(g0.x), as_f32(g0.y), as_f32(g0.z), as_f32(g0.w), as_f32(g1.x), as_f32(g1.y), as_f32(g1.z), as_f32(g1.w)};
+    float wf[8] = {as_f32(w0.x), as_f32(w0.y), as_f32(w0.z), as_f32(w0.w), as_f32(w1.x), as_f32(w1.y), as_f32(w1.z), as_f32(w1.w)};
+    float mf[8], vf[8];
+    widen<Bf16>(mm, mf);
+    widen<Bf16>(vv, vf);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        mf[e] = a.beta1 * mf[e] + (1.0f - a.beta1) * gf[e];
+        vf[e] = a.beta2 * vf[e] + (1.0f - a.beta2) * (gf[e] * gf[e]);
+        const float mhat = mf[e] * a.rbc1, vhat = vf[e] * a.rbc2;
+        wf[e] = wf[e] - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.wd * wf[e]);
+    }
+    st_stream(reinterpret_cast<uint8_t*>(w) + i * 32, u32x4{as_u32(wf[0]), as_u32(wf[1]), as_u32(wf[2]), as_u32(wf[3])});
+    st_stream(reinterpret_cast<uint8_t*>(w) + i * 32 + 16, u32x4{as_u32(wf[4]), as_u32(wf[5]), as_u32(wf[6]), as_u32(wf[7])});
+    st_stream(m + i * 16, u32x4{pack_bf16x2(mf[0], mf[1]), pack_bf16x2(mf[2], mf[3]), pack_bf16x2(mf[4], mf[5]), pack_bf16x2(mf[6], mf[7])});
+    st_stream(v + i * 16, u32x4{pack_bf16x2(vf[0], vf[1]), pack_bf16x2(vf[2], vf[3]), pack_bf16x2(vf[4], vf[5]), pack_bf16x2(vf[6], vf[7])});
+    if (wb != nullptr)
+        st_stream(wb + i * 16, u32x4{pack_bf16x2(wf[0], wf[1]), pack_bf16x2(wf[2], wf[3]), pack_bf16x2(wf[4], wf[5]), pack_bf16x2(wf[6], wf[7])});
+}
+
 // ----- host launchers -----------------------------------------------------------
 static ds3_status launch_status() { return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH; }
 
@@ -727,6 +767,14 @@ ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t 
                                         int64_t sst, int pow2, hipStream_t st) {
     dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
     retile_1x128_to_128x1_kernel<<<grid, 256, 0, st>>>(q, rows, cols, ldq, s, ssr, ssk, qt, ldqt, s_t, ssc, sst, pow2);
+    return launch_status();
+}
+
+ds3_status launch_adamw_bf16_states(int64_t n, float* w, const float* g, void* m, void* v, void* wb, float lr, float beta1,
+                                    float beta2, float eps, float wd, float rbc1, float rbc2, hipStream_t st) {
+    const int64_t n8 = n / 8;
+    AdamwArgs a{lr, beta1, beta2, eps, wd, rbc1, rbc2};
+    adamw_bf16_states_kernel<<<dim3((unsigned)((n8 + 255) / 256)), 256, 0, st>>>(n8, w, g, (uint8_t*)m, (uint8_t*)v, (uint8_t*)wb, a);
     return launch_status();
 }
 
