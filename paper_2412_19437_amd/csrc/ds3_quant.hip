@@ -567,70 +567,84 @@ __global__ __launch_bounds__(256) void swiglu_quant_1x128_kernel(
 constexpr int kNormMaxGranules = 4;               // 16-byte granules per lane: rows of up to 4 * 2048 elements
 
 __global__ __launch_bounds__(256) void rmsnorm_quant_1x128_kernel(
-    const uint8_t* __restrict__ x, int64_t cols, int64_t ldx_bytes, const float* __restrict__ gamma,
+    const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes, const float* __restrict__ gamma,
     float eps, uint8_t* __restrict__ y, int64_t ldy_bytes, uint8_t* __restrict__ q, int64_t ldq,
     float* __restrict__ s, int64_t ssr, int64_t ssk, int pow2) {
-    __shared__ float red[4];
+    __shared__ float red[2][4];
     const int lane16 = threadIdx.x & 15, t16 = threadIdx.x >> 4;
-    const int64_t row = blockIdx.x;
-    const uint8_t* xr = x + row * ldx_bytes;
 
-    // granule i of this lane: tile 16*i + t16, elements [lane16*8, +8) of it
-    u32x4 g[kNormMaxGranules];
+    // granule i of this lane: tile 16*i + t16, elements [lane16*8, +8) of it; the gains stay in registers
+    // for all the rows this workgroup walks
     f32x4 gm[kNormMaxGranules][2];
-    float ss = 0.f;
+    bool ok[kNormMaxGranules];
 #pragma unroll
     for (int i = 0; i < kNormMaxGranules; ++i) {
         const int64_t col = ((int64_t)(16 * i + t16) << 7) + lane16 * 8;
-        g[i] = u32x4{0u, 0u, 0u, 0u};
+        ok[i] = col < cols;
         gm[i][0] = gm[i][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (col < cols) {
-            g[i] = ld_stream(xr + col * 2);
+        if (ok[i]) {
             gm[i][0] = *reinterpret_cast<const f32x4*>(gamma + col);
             gm[i][1] = *reinterpret_cast<const f32x4*>(gamma + col + 4);
         }
     }
+    auto load_row = [&](int64_t row, u32x4* g) {
 #pragma unroll
-    for (int i = 0; i < kNormMaxGranules; ++i) {
-        float v[8];
-        widen<Bf16>(g[i], v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(v[e], v[e], ss);
-    }
-    // sum over the workgroup: butterflies inside the 16-lane rows, across the wave's four rows, then LDS
-    ss += as_f32(dpp_u32<0xB1>(as_u32(ss)));
-    ss += as_f32(dpp_u32<0x4E>(as_u32(ss)));
-    ss += as_f32(dpp_u32<0x141>(as_u32(ss)));
-    ss += as_f32(dpp_u32<0x140>(as_u32(ss)));
-    ss += __shfl_xor(ss, 16);
-    ss += __shfl_xor(ss, 32);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    ss = (red[0] + red[1]) + (red[2] + red[3]);
-    const float rstd = 1.0f / sqrtf(ss / (float)cols + eps);
+        for (int i = 0; i < kNormMaxGranules; ++i) {
+            const int64_t col = ((int64_t)(16 * i + t16) << 7) + lane16 * 8;
+            g[i] = u32x4{0u, 0u, 0u, 0u};
+            if (ok[i] && row < rows) g[i] = ld_stream(x + row * ldx_bytes + col * 2);
+        }
+    };
 
+    u32x4 g[kNormMaxGranules], gn[kNormMaxGranules];
+    int64_t row = blockIdx.x;
+    load_row(row, g);
+    for (int it = 0; row < rows; row += gridDim.x, ++it) {
+        load_row(row + gridDim.x, gn);            // the next row travels while this one is worked on
+        float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < kNormMaxGranules; ++i) {
-        const int64_t kb = 16 * i + t16;
-        const int64_t col = (kb << 7) + lane16 * 8;
-        if ((kb << 7) < cols) {                   // a whole DPP row decides together
-            const bool ok = col < cols;
+        for (int i = 0; i < kNormMaxGranules; ++i) {
             float v[8];
             widen<Bf16>(g[i], v);
-            const float gmv[8] = {gm[i][0].x, gm[i][0].y, gm[i][0].z, gm[i][0].w, gm[i][1].x, gm[i][1].y, gm[i][1].z, gm[i][1].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] * rstd * gmv[e];
-            const u32x4 w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-            if (y != nullptr && ok) st_stream(y + row * ldy_bytes + col * 2, w);
-            const unsigned int m = row16_max_bits(granule_amax_bits<Bf16>(w));
-            const GroupScale gs = group_scale(as_f32(m), pow2);
-            if (lane16 == 0) s[row * ssr + kb * ssk] = gs.s;
-            float r[8];
-            widen<Bf16>(w, r);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) r[e] = r[e] * gs.r;
-            if (ok) st_stream(q + row * ldq + col, u32x2{cvt4_e4m3(r[0], r[1], r[2], r[3]), cvt4_e4m3(r[4], r[5], r[6], r[7])});
+            for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(v[e], v[e], ss);
         }
+        // sum over the workgroup: butterflies inside the 16-lane rows, across the wave's four rows, then LDS
+        ss += as_f32(dpp_u32<0xB1>(as_u32(ss)));
+        ss += as_f32(dpp_u32<0x4E>(as_u32(ss)));
+        ss += as_f32(dpp_u32<0x141>(as_u32(ss)));
+        ss += as_f32(dpp_u32<0x140>(as_u32(ss)));
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if ((threadIdx.x & 63) == 0) red[it & 1][threadIdx.x >> 6] = ss;
+        __syncthreads();                          // the two halves of `red` alternate: one barrier per row suffices
+        ss = (red[it & 1][0] + red[it & 1][1]) + (red[it & 1][2] + red[it & 1][3]);
+        const float rstd = 1.0f / sqrtf(ss / (float)cols + eps);
+
+#pragma unroll
+        for (int i = 0; i < kNormMaxGranules; ++i) {
+            const int64_t kb = 16 * i + t16;
+            const int64_t col = (kb << 7) + lane16 * 8;
+            if ((kb << 7) < cols) {               // a whole DPP row decides together
+                float v[8];
+                widen<Bf16>(g[i], v);
+                const float gmv[8] = {gm[i][0].x, gm[i][0].y, gm[i][0].z, gm[i][0].w, gm[i][1].x, gm[i][1].y, gm[i][1].z, gm[i][1].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = v[e] * rstd * gmv[e];
+                const u32x4 w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+                if (y != nullptr && ok[i]) st_stream(y + row * ldy_bytes + col * 2, w);
+                const unsigned int m = row16_max_bits(granule_amax_bits<Bf16>(w));
+                const GroupScale gs = group_scale(as_f32(m), pow2);
+                if (lane16 == 0) s[row * ssr + kb * ssk] = gs.s;
+                float r[8];
+                widen<Bf16>(w, r);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = r[e] * gs.r;
+                if (ok[i]) st_stream(q + row * ldq + col, u32x2{cvt4_e4m3(r[0], r[1], r[2], r[3]), cvt4_e4m3(r[4], r[5], r[6], r[7])});
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kNormMaxGranules; ++i) g[i] = gn[i];
     }
 }
 
@@ -782,8 +796,10 @@ ds3_status launch_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols,
                                       void* y, int64_t ldy, uint8_t* q, int64_t ldq, float* s, int64_t ssr, int64_t ssk,
                                       int pow2, hipStream_t st) {
     if (cols > (int64_t)kNormMaxGranules * 2048) return DS3_ERR_UNSUPPORTED;
-    rmsnorm_quant_1x128_kernel<<<dim3((unsigned)rows), 256, 0, st>>>(
-        (const uint8_t*)x, cols, ldx * 2, gamma, eps, (uint8_t*)y, ldy * 2, q, ldq, s, ssr, ssk, pow2);
+    // four workgroups per compute unit (all resident at once), each walking rows a grid apart
+    const int64_t grid = rows < 1024 ? rows : 1024;
+    rmsnorm_quant_1x128_kernel<<<dim3((unsigned)grid), 256, 0, st>>>(
+        (const uint8_t*)x, rows, cols, ldx * 2, gamma, eps, (uint8_t*)y, ldy * 2, q, ldq, s, ssr, ssk, pow2);
     return launch_status();
 }
 
