@@ -82,3 +82,48 @@ def test_gemm_rejects_bad_arguments_on_the_host(pkg):
     assert L.ds3_swiglu(p, 4, 12, 24, p, 16, None) == 3
     assert L.ds3_swiglu(None, 4, 16, 32, p, 16, None) == 1
     assert pkg.ds3_gemm_workspace_bytes(4096, 18432, 7168) == 0
+
+
+def test_later_entry_points_reject_bad_arguments_on_the_host(pkg):
+    L = pkg._L()
+    buf = (ctypes.c_uint8 * 4096)()
+    p = (ctypes.addressof(buf) + 15) & ~15
+    # power-of-two forms share the checks of the plain calls
+    assert L.ds3_quant_act_1x128_pow2(None, 1, 4, 128, 128, p, 128, p, 1, 4, None) == 1
+    assert L.ds3_gemm_fp8_bs_pow2(-1, 16, 16, 100, p, 128, p, 1, 16, p, 128, p, 1, 1, 0, p, 1, 16, 0, None, 0, None) == 2
+    assert L.ds3_gemm_fp8_bs_pow2(7, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, 1, 1, 0, p, 1, 16, 0, None, 0, None) == 5
+    assert L.ds3_grouped_gemm_fp8_bs_pow2(-1, 1, None, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, p, 1, 16, None, 0, None) == 1
+    # dual-layout weight quantizer
+    d = L.ds3_quant_w_128x128_dual
+    assert d(p, 1, 16, 128, 128, p, 128, p, None, 16, p, None) == 1           # q_t missing
+    assert d(p, 1, 16, 128, 128, p, 128, p, p, 8, p, None) == 2               # ldqt < n
+    assert d(p, 1, 20, 128, 128, p, 128, p, p, 24, p, None) == 3              # ldqt % 16
+    assert d(p, 1, 0, 128, 128, None, 128, None, None, 0, None, None) == 0    # empty
+    # cache re-tiling
+    r = L.ds3_retile_1x128_to_128x1
+    assert r(p, 16, 128, 128, None, 1, 16, p, 16, p, 1, 128, None) == 1
+    assert r(p, 16, 136, 144, p, 1, 16, p, 16, p, 1, 136, None) == 3          # cols % 16
+    assert r(p, 16, 128, 64, p, 1, 16, p, 16, p, 1, 128, None) == 2           # ldq < cols
+    assert r(p, 20, 128, 128, p, 1, 20, p, 16, p, 1, 128, None) == 2          # ldqt < rows
+    assert r(p, -1, 128, 128, p, 1, 16, p, 16, p, 1, 128, None) == 2
+    # fused producers
+    sq = L.ds3_swiglu_quant_1x128
+    assert sq(p, 4, 12, 24, p, 16, p, 1, 4, None) == 3                        # inter % 8
+    assert sq(p, 4, 16, 24, p, 16, p, 1, 4, None) == 2                        # ldh < 2 * inter
+    assert sq(p, 4, 16, 32, None, 16, p, 1, 4, None) == 1
+    rn = L.ds3_rmsnorm_quant_1x128
+    assert rn(p, 4, 128, 128, None, 1e-6, None, 0, p, 128, p, 1, 4, None) == 1      # gamma missing
+    assert rn(p, 4, 8200, 8200, p, 1e-6, None, 0, p, 8208, p, 1, 4, None) == 5      # row longer than 8192
+    assert rn(p, 4, 128, 128, p, -1.0, None, 0, p, 128, p, 1, 4, None) == 2         # negative eps
+    assert rn(p, 4, 128, 128, p, 1e-6, p, 64, p, 128, p, 1, 4, None) == 2           # ldy < cols
+    # optimizer
+    ad = L.ds3_adamw_bf16_states
+    assert ad(16, p, p, p, p, None, 1e-3, 0.9, 0.95, 1e-8, 0.1, 0, None) == 2       # steps count from 1
+    assert ad(12, p, p, p, p, None, 1e-3, 0.9, 0.95, 1e-8, 0.1, 1, None) == 3       # n % 8
+    assert ad(16, p, p, p, p, None, 1e-3, 1.0, 0.95, 1e-8, 0.1, 1, None) == 2       # beta1 == 1
+    assert ad(16, None, p, p, p, None, 1e-3, 0.9, 0.95, 1e-8, 0.1, 1, None) == 1
+    assert ad(0, None, None, None, None, None, 1e-3, 0.9, 0.95, 1e-8, 0.1, 1, None) == 0
+    # probes
+    assert L.ds3_probe_mfma_fp8(10, 4, None, None) == 1
+    assert L.ds3_probe_lds_feed(p, 1 << 20, 100, 10, 4, p, None) == 2               # row stride not a multiple of 128
+    assert L.ds3_probe_lds_feed(p, 1 << 20, 7168, 10, 4, p, None) == 5              # window smaller than 4096 rows
