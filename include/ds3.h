@@ -323,6 +323,28 @@ ds3_status ds3_rmsnorm_quant_1x128_pow2(const void* x, int64_t rows, int64_t col
                                         float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
 
 /*
+ * E5M6 activation cache (Section 3.3.3, Low-Precision Activation (1): the inputs
+ * of the Linear after the attention operator are cached in a customized 12-bit
+ * E5M6 format with 1x128 tiles and power-of-two scaling factors).  The report
+ * gives no bit layout; this library's encoding is: sign, 5 exponent bits with
+ * bias 15, 6 mantissa bits -- the upper 12 bits of IEEE binary16 -- exponent
+ * field 0 subnormal (mantissa * 2^-20), exponent field 31 never produced,
+ * largest magnitude 65024; codes a (even column) and b (odd column) share three
+ * bytes: a[7:0], a[11:8] | b[3:0] << 4, b[11:4].
+ *   quantizer:   x [rows][ldx] BF16 -> q [rows][ldq] bytes (3 * cols / 2 valid per row),
+ *                s as in ds3_quant_act_1x128 with  s = smallest power of two >= amax / 65024
+ *                (1 for an all-zero tile), q_i = E5M6_round_to_nearest_even(x_i / s).
+ *   dequantizer: y [rows][ldy] BF16 = decode(q) * s, exact (7 significant bits times a power of two).
+ * cols % 8 == 0; x, y 16-byte aligned, ldx, ldy % 8 == 0; q 4-byte aligned, ldq % 4 == 0.
+ */
+ds3_status ds3_quant_act_1x128_e5m6(const void* x, int64_t rows, int64_t cols, int64_t ldx,
+                                    uint8_t* q, int64_t ldq,
+                                    float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+ds3_status ds3_dequant_e5m6(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq,
+                            const float* s, int64_t s_stride_row, int64_t s_stride_kb,
+                            void* y, int64_t ldy, void* stream);
+
+/*
  * AdamW step with low-precision optimizer states (Section 3.3.3: the first and
  * second moments are kept in BF16, master weights and gradients in FP32;
  * Section 4.2 gives beta1 = 0.9, beta2 = 0.95, weight_decay = 0.1).  For every

@@ -39,8 +39,17 @@ all finite codes, every midpoint tie, brute-force nearest-neighbour search,
 PyTorch's CPU float8_e4m3fn cast as a third opinion, an independent
 exact-rational implementation of the quantizers and the GEMM on tiny shapes,
 power-of-two exactness, scale-invariance, transposition identities, and the
-"all scales 1 equals the plain product" identity.  No function in this file
-is parity-unpinned.
+"all scales 1 equals the plain product" identity; for the later additions:
+the library optimizer in FP64 and the first step's closed form (AdamW), the
+library RMSNorm, the library BF16 cast, composition identities of the fused
+producers, and binary16's upper twelve bits plus brute-force nearest search
+(E5M6 arithmetic).
+
+PARITY UNPINNED: the bit layout and byte packing of the E5M6 cache format
+(e5m6_* and quant_act_1x128_e5m6 / dequant_e5m6).  The report names the format
+and its use but prints no layout; the one here is this build's proposal.  Its
+arithmetic (rounding, scales, error bound) is pinned, its layout cannot be.
+Every other function in this file is pinned.
 """
 from __future__ import annotations
 
@@ -308,3 +317,98 @@ def adamw_step(w, g, m, v, lr, beta1, beta2, eps, weight_decay, step, bf16_momen
         return w, m, v, w
     w32 = w.astype(np.float32)
     return w32, round_to_bf16(m), round_to_bf16(v), round_to_bf16(w32)
+
+
+# --------------------------------------------------------------------------
+# E5M6 activation cache (Section 3.3.3, Low-Precision Activation (1)).
+# The report names the format (a customized 12-bit E5M6 for the inputs of the
+# Linear after attention, with power-of-two 1x128 scaling factors) but gives no
+# bit layout.  PROPOSED ENCODING of this build -- parity unpinned as far as the
+# layout goes: 1 sign bit, 5 exponent bits (bias 15), 6 mantissa bits, i.e. the
+# upper 12 bits of IEEE binary16: exponent field 0 is subnormal (mantissa *
+# 2^-20), exponent field 31 is reserved and never produced, so the largest
+# magnitude is (2 - 2^-6) * 2^15 = 65024.  Two codes a, b are packed into three
+# bytes: a[7:0], a[11:8] | b[3:0] << 4, b[11:4].
+# --------------------------------------------------------------------------
+E5M6_MAX = 65024.0
+
+
+def e5m6_decode(codes) -> np.ndarray:
+    """Exact value of each 12-bit E5M6 code (uint16 array) as float64; reserved codes give NaN."""
+    c = np.asarray(codes).astype(np.int64)
+    sign = np.where((c & 0x800) != 0, -1.0, 1.0)
+    efield = (c >> 6) & 0x1F
+    mant = (c & 0x3F).astype(np.float64)
+    normal = np.ldexp(1.0 + mant / 64.0, (efield - 15).astype(np.int64))
+    val = sign * np.where(efield == 0, mant * 2.0 ** -20, normal)
+    return np.where(efield == 31, np.nan, val)
+
+
+def e5m6_encode_rne_sat(y) -> np.ndarray:
+    """Round finite values to the nearest E5M6 value, ties to the even code,
+    saturating at +-65024; the sign bit of the input is always copied."""
+    y = np.asarray(y)
+    if not np.all(np.isfinite(y)):
+        raise ValueError("oracle precondition: finite inputs")
+    neg = np.signbit(y)
+    a = np.abs(y.astype(np.float64))
+    _, ex = np.frexp(a)
+    e = np.maximum(ex.astype(np.int64) - 1, -14)
+    quantum = np.ldexp(1.0, e - 6)
+    v = np.minimum(np.rint(a / quantum) * quantum, E5M6_MAX)
+    _, ex2 = np.frexp(v)
+    e2 = ex2.astype(np.int64) - 1
+    sub = v < 2.0 ** -14
+    sub_code = np.rint(v * 2.0 ** 20).astype(np.int64)
+    mant = np.rint((v / np.ldexp(1.0, e2) - 1.0) * 64.0).astype(np.int64)
+    code = np.where(sub, sub_code, ((e2 + 15) << 6) | mant)
+    return np.where(neg, code | 0x800, code).astype(np.uint16)
+
+
+def e5m6_pack(codes) -> np.ndarray:
+    """[rows][k] 12-bit codes (k even) -> [rows][3k/2] bytes."""
+    c = np.asarray(codes).astype(np.uint32)
+    a, b = c[:, 0::2], c[:, 1::2]
+    out = np.empty((c.shape[0], c.shape[1] // 2, 3), np.uint8)
+    out[:, :, 0] = a & 0xFF
+    out[:, :, 1] = (a >> 8) | ((b & 0xF) << 4)
+    out[:, :, 2] = b >> 4
+    return out.reshape(c.shape[0], -1)
+
+
+def e5m6_unpack(packed) -> np.ndarray:
+    p = np.asarray(packed, dtype=np.uint8).astype(np.uint16).reshape(packed.shape[0], -1, 3)
+    a = p[:, :, 0] | ((p[:, :, 1] & 0xF) << 8)
+    b = (p[:, :, 1] >> 4) | (p[:, :, 2] << 4)
+    return np.stack([a, b], axis=2).reshape(packed.shape[0], -1)
+
+
+def quant_act_1x128_e5m6(x):
+    """1x128 tiles, power-of-two scale = the smallest power of two >= amax / 65024
+    (1 for an all-zero tile), elements times its exact reciprocal, rounded to
+    E5M6.  x float32 [M][K], K even.  Returns (packed codes uint8 [M][3K/2],
+    scales float32 [M][ceil(K/128)])."""
+    x = np.asarray(x)
+    if x.dtype != np.float32:
+        raise TypeError("quantizer input must be float32 (BF16 widens exactly)")
+    m, k = x.shape
+    kb = (k + TILE - 1) // TILE
+    xp = np.zeros((m, kb * TILE), np.float32)
+    xp[:, :k] = x
+    xg = xp.reshape(m, kb, TILE)
+    amax = np.max(np.abs(xg), axis=2, keepdims=True)
+    zero = amax == 0
+    mant, ex = np.frexp(np.where(zero, 1.0, amax).astype(np.float64) / E5M6_MAX)
+    e = np.where(mant == 0.5, ex - 1, ex)
+    s = np.where(zero, 1.0, np.ldexp(1.0, e)).astype(np.float32)
+    y = (xg * np.where(zero, 0.0, np.ldexp(1.0, -e)).astype(np.float32)).astype(np.float32)
+    codes = e5m6_encode_rne_sat(y).reshape(m, kb * TILE)[:, :k]
+    return e5m6_pack(codes), s.reshape(m, kb)
+
+
+def dequant_e5m6(packed, scales) -> np.ndarray:
+    """decode * scale, float64 [M][K]."""
+    codes = e5m6_unpack(packed)
+    k = codes.shape[1]
+    s = np.repeat(np.asarray(scales, dtype=np.float32).astype(np.float64), TILE, axis=1)[:, :k]
+    return e5m6_decode(codes) * s

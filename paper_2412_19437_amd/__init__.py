@@ -31,6 +31,7 @@ SYMBOLS = [
     "ds3_retile_1x128_to_128x1", "ds3_retile_1x128_to_128x1_pow2",
     "ds3_quant_w_128x128_dual", "ds3_quant_w_128x128_dual_pow2",
     "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2", "ds3_adamw_bf16_states",
+    "ds3_quant_act_1x128_e5m6", "ds3_dequant_e5m6",
 ]
 
 
@@ -69,6 +70,8 @@ def _load() -> ctypes.CDLL:
     f32 = ctypes.c_float
     lib.ds3_rmsnorm_quant_1x128.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_rmsnorm_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, f32, vp, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_quant_act_1x128_e5m6.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    lib.ds3_dequant_e5m6.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp]
     lib.ds3_adamw_bf16_states.argtypes = [i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, vp]
     lib.ds3_probe_mfma_fp8.argtypes = [i32, i32, vp, vp]
     lib.ds3_probe_lds_feed.argtypes = [vp, sz, i64, i32, i32, vp, vp]
@@ -315,6 +318,29 @@ def ds3_rmsnorm_quant_1x128(x, gamma, eps: float = 1e-6, want_y: bool = False, k
 def ds3_rmsnorm_quant_1x128_pow2(x, gamma, eps: float = 1e-6, want_y: bool = False, k_major_scales: bool = True):
     """As ds3_rmsnorm_quant_1x128 with power-of-two scales."""
     return _rmsnorm_quant("ds3_rmsnorm_quant_1x128_pow2", x, gamma, eps, want_y, k_major_scales)
+
+
+def ds3_quant_act_1x128_e5m6(x: torch.Tensor, k_major_scales: bool = True):
+    """x [M][K] BF16 -> (packed E5M6 codes uint8 [M][3K/2], power-of-two scales logical [M][ceil(K/128)])."""
+    m, k, ldx = _rows2d(x, "x")
+    if x.dtype != torch.bfloat16:
+        raise TypeError("x must be BF16")
+    q = torch.empty((m, k * 3 // 2), dtype=torch.uint8, device=x.device)
+    s = _scales(m, (k + 127) // 128, x.device, k_major_scales)
+    st = _L().ds3_quant_act_1x128_e5m6(x.data_ptr(), m, k, ldx, q.data_ptr(), k * 3 // 2, s.data_ptr(), s.stride(0),
+                                      s.stride(1), _stream())
+    _check(st, "ds3_quant_act_1x128_e5m6")
+    return q, s
+
+
+def ds3_dequant_e5m6(q: torch.Tensor, s: torch.Tensor):
+    """Packed E5M6 codes [M][3K/2] and scales -> BF16 [M][K]."""
+    m, kb3, ldq = _rows2d(q, "q")
+    k = kb3 * 2 // 3
+    y = torch.empty((m, k), dtype=torch.bfloat16, device=q.device)
+    st = _L().ds3_dequant_e5m6(q.data_ptr(), m, k, ldq, s.data_ptr(), s.stride(0), s.stride(1), y.data_ptr(), k, _stream())
+    _check(st, "ds3_dequant_e5m6")
+    return y
 
 
 def ds3_adamw_bf16_states(master_w, grad, m, v, lr, beta1, beta2, eps, weight_decay, step, w_bf16=None):

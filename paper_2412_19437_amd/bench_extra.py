@@ -259,6 +259,8 @@ def _fused(ds3, torch, wl, dev, variant):
         for k in kernels:
             k(record)
 
+    kernels.append(Timed("quant_act_1x128_e5m6(X 4096x7168)", lambda: ds3.ds3_quant_act_1x128_e5m6(x), "GB/s",
+                         (T * H * 3.5 + groups(T, H) * 4) / 1e9, "hbm", PEAK_HBM_GBS))
     # AdamW with BF16 moments on the layer's 132 M parameters: 22 bytes of traffic per parameter
     nparam = I * H
     mw = torch.randn(nparam, generator=gen, device=dev) * 0.02

@@ -242,6 +242,29 @@ ds3_status ds3_retile_1x128_to_128x1_pow2(const uint8_t* q, int64_t rows, int64_
     return retile(1, q, rows, cols, ldq, s, s_stride_row, s_stride_kb, q_t, ldqt, s_t, st_stride_col, st_stride_tb, stream);
 }
 
+ds3_status ds3_quant_act_1x128_e5m6(const void* x, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q, int64_t ldq, float* s,
+                                    int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return DS3_OK;
+    if (!x || !q || !s) return DS3_ERR_NULL;
+    if (ldx < cols || ldq < cols * 3 / 2) return DS3_ERR_SHAPE;
+    if (!aligned16(x) || (reinterpret_cast<uintptr_t>(q) & 3u) || cols % 8 || ldx % 8 || ldq % 4) return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || cols > kMaxDim) return DS3_ERR_UNSUPPORTED;
+    return launch_quant_act_1x128_e5m6(x, rows, cols, ldx, q, ldq, s, s_stride_row, s_stride_kb,
+                                       static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_dequant_e5m6(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s, int64_t s_stride_row,
+                            int64_t s_stride_kb, void* y, int64_t ldy, void* stream) {
+    if (rows < 0 || cols < 0) return DS3_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return DS3_OK;
+    if (!q || !s || !y) return DS3_ERR_NULL;
+    if (ldy < cols || ldq < cols * 3 / 2) return DS3_ERR_SHAPE;
+    if (!aligned16(y) || (reinterpret_cast<uintptr_t>(q) & 3u) || cols % 8 || ldy % 8 || ldq % 4) return DS3_ERR_ALIGN;
+    if (rows > kMaxDim || cols > kMaxDim) return DS3_ERR_UNSUPPORTED;
+    return launch_dequant_e5m6(q, rows, cols, ldq, s, s_stride_row, s_stride_kb, y, ldy, static_cast<hipStream_t>(stream));
+}
+
 ds3_status ds3_adamw_bf16_states(int64_t n, float* master_w, const float* grad, void* m, void* v, void* w_bf16, float lr,
                                  float beta1, float beta2, float eps, float weight_decay, int64_t step, void* stream) {
     if (n < 0 || step < 1) return DS3_ERR_SHAPE;

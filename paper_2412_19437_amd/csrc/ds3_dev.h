@@ -67,6 +67,42 @@ __device__ __forceinline__ GroupScale group_scale(float amax, int pow2) {
     return g;
 }
 
+// E5M6 (12-bit cache format: sign, 5 exponent bits with bias 15, 6 mantissa bits; the
+// upper 12 bits of IEEE binary16, exponent field 31 never produced): round to nearest
+// even from FP32, saturating at 65024.  Normal results round the FP32 significand in
+// place; results below 2^-14 are rounded by an FP32 addition whose ulp is the subnormal
+// quantum 2^-20.
+__device__ __forceinline__ unsigned int e5m6_rne(float y) {
+    unsigned int u = as_u32(y);
+    const unsigned int sign = (u >> 20) & 0x800u;
+    u &= 0x7fffffffu;
+    unsigned int code;
+    if (u >= 0x38800000u) {                       // |y| >= 2^-14
+        u += 0xffffu + ((u >> 17) & 1u);
+        code = (u >> 17) - (112u << 6);
+        code = code < 0x7bfu ? code : 0x7bfu;
+    } else {
+        code = as_u32(as_f32(u) + 8.0f) - as_u32(8.0f);
+    }
+    return sign | code;
+}
+__device__ __forceinline__ float e5m6_decode(unsigned int c) {
+    const unsigned int mag = c & 0x7ffu;
+    // exponent field 0: mantissa * 2^-20 (exact in FP32); otherwise re-bias into FP32
+    const float v = mag < 64u ? (float)mag * 9.5367431640625e-07f : as_f32((mag << 17) + (112u << 23));
+    return (c & 0x800u) ? -v : v;
+}
+// The smallest power of two >= amax / 65024 and its reciprocal (65024 = (2 - 2^-6) * 2^15).
+__device__ __forceinline__ GroupScale group_scale_e5m6(float amax) {
+    GroupScale g;
+    if (amax == 0.0f) { g.s = 1.0f; g.r = 0.0f; return g; }
+    const unsigned int bits = as_u32(amax);
+    const unsigned int e = (bits >> 23) - 15u + ((bits & 0x7fffffu) > 0x7e0000u ? 1u : 0u);
+    g.s = as_f32(e << 23);
+    g.r = as_f32((254u - e) << 23);
+    return g;
+}
+
 // silu(g) * u in FP32 with the hardware reciprocal (1 ulp) instead of an IEEE
 // division: the result is rounded to BF16 (8 significant bits) by every caller,
 // and all callers share this one expression so that they agree bit for bit.

@@ -22,6 +22,10 @@ ds3_status launch_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh
 ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s,
                                         int64_t ssr, int64_t ssk, uint8_t* qt, int64_t ldqt, float* s_t, int64_t ssc,
                                         int64_t sst, int pow2, hipStream_t st);
+ds3_status launch_quant_act_1x128_e5m6(const void* x, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q, int64_t ldq,
+                                       float* s, int64_t ssr, int64_t ssk, hipStream_t st);
+ds3_status launch_dequant_e5m6(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s, int64_t ssr,
+                               int64_t ssk, void* y, int64_t ldy, hipStream_t st);
 ds3_status launch_adamw_bf16_states(int64_t n, float* w, const float* g, void* m, void* v, void* wb, float lr, float beta1,
                                     float beta2, float eps, float wd, float rbc1, float rbc2, hipStream_t st);
 ds3_status launch_rmsnorm_quant_1x128(const void* x, int64_t rows, int64_t cols, int64_t ldx, const float* gamma, float eps,

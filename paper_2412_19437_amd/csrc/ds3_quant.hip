@@ -649,6 +649,72 @@ __global__ __launch_bounds__(256) void rmsnorm_quant_1x128_kernel(
 }
 
 // =============================================================================
+// E5M6 activation cache (Section 3.3.3 (1)): 1x128 tiles with power-of-two scales,
+// two 12-bit codes per three bytes.  One 16-lane DPP row per tile as in the E4M3
+// quantizer; a lane's eight codes are 12 contiguous bytes, a tile 192.
+// =============================================================================
+template <int TPG>
+__global__ __launch_bounds__(256) void quant_act_1x128_e5m6_kernel(
+    const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx_bytes,
+    uint8_t* __restrict__ q, int64_t ldq, float* __restrict__ s, int64_t ssr, int64_t ssk) {
+    const int lane16 = threadIdx.x & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (row >= rows) return;
+    const int64_t kb0 = (int64_t)blockIdx.y * TPG;
+    const int64_t nkb = (cols + 127) >> 7;
+    const uint8_t* xr = x + row * ldx_bytes;
+    u32x4 g[TPG];
+    bool ok[TPG];
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+        const int64_t col = (kb0 + t) * 128 + lane16 * 8;
+        ok[t] = col < cols;
+        g[t] = u32x4{0u, 0u, 0u, 0u};
+        if (ok[t]) g[t] = ld_stream(xr + col * 2);
+    }
+#pragma unroll
+    for (int t = 0; t < TPG; ++t) {
+        if (kb0 + t >= nkb) break;
+        const unsigned int m = row16_max_bits(granule_amax_bits<Bf16>(g[t]));
+        const GroupScale gs = group_scale_e5m6(as_f32(m));
+        if (lane16 == 0) s[row * ssr + (kb0 + t) * ssk] = gs.s;
+        float v[8];
+        widen<Bf16>(g[t], v);
+        unsigned int c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = e5m6_rne(v[i] * gs.r);
+        if (ok[t]) {
+            // 8 codes of 12 bits -> 3 words, code i at bit 12*i
+            const int64_t col = (kb0 + t) * 128 + lane16 * 8;
+            unsigned int* dst = reinterpret_cast<unsigned int*>(q + row * ldq + col * 3 / 2);   // 4-byte aligned, 12 bytes
+            dst[0] = c[0] | (c[1] << 12) | (c[2] << 24);
+            dst[1] = (c[2] >> 8) | (c[3] << 4) | (c[4] << 16) | (c[5] << 28);
+            dst[2] = (c[5] >> 4) | (c[6] << 8) | (c[7] << 20);
+        }
+    }
+}
+
+// packed E5M6 codes + scales -> BF16 (exact: 7 significant bits times a power of two)
+__global__ __launch_bounds__(256) void dequant_e5m6_kernel(const uint8_t* __restrict__ q, int64_t rows, int64_t cols, int64_t ldq,
+                                                           const float* __restrict__ s, int64_t ssr, int64_t ssk,
+                                                           uint8_t* __restrict__ y, int64_t ldy_bytes) {
+    const int64_t gpr = cols >> 3;                                   // 8-element granules per row
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows * gpr) return;
+    const int64_t row = idx / gpr, gi = idx - row * gpr;
+    const unsigned int* src = reinterpret_cast<const unsigned int*>(q + row * ldq + gi * 12);   // 4-byte aligned, 12 bytes
+    const unsigned int w0 = src[0], w1 = src[1], w2 = src[2];
+    const float sc = s[row * ssr + (gi >> 4) * ssk];
+    const unsigned int c[8] = {w0 & 0xfffu, (w0 >> 12) & 0xfffu, ((w0 >> 24) | (w1 << 8)) & 0xfffu, (w1 >> 4) & 0xfffu,
+                               (w1 >> 16) & 0xfffu, ((w1 >> 28) | (w2 << 4)) & 0xfffu, (w2 >> 8) & 0xfffu, w2 >> 20};
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = e5m6_decode(c[i]) * sc;
+    st_stream(y + row * ldy_bytes + gi * 16,
+              u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])});
+}
+
+// =============================================================================
 // AdamW step with BF16 first and second moments, FP32 master weights and FP32
 // gradients (Section 3.3.3, Low-Precision Optimizer States).  One pass over the
 // parameters: 8 per thread, 16-byte accesses.  The moments are updated in FP32
@@ -781,6 +847,22 @@ ds3_status launch_retile_1x128_to_128x1(const uint8_t* q, int64_t rows, int64_t 
                                         int64_t sst, int pow2, hipStream_t st) {
     dim3 grid((unsigned)((cols + 127) / 128), (unsigned)((rows + 127) / 128));
     retile_1x128_to_128x1_kernel<<<grid, 256, 0, st>>>(q, rows, cols, ldq, s, ssr, ssk, qt, ldqt, s_t, ssc, sst, pow2);
+    return launch_status();
+}
+
+ds3_status launch_quant_act_1x128_e5m6(const void* x, int64_t rows, int64_t cols, int64_t ldx, uint8_t* q, int64_t ldq,
+                                       float* s, int64_t ssr, int64_t ssk, hipStream_t st) {
+    constexpr int TPG = 4;
+    const int64_t nkb = (cols + 127) / 128;
+    dim3 grid((unsigned)((rows + 15) / 16), (unsigned)((nkb + TPG - 1) / TPG));
+    quant_act_1x128_e5m6_kernel<TPG><<<grid, 256, 0, st>>>((const uint8_t*)x, rows, cols, ldx * 2, q, ldq, s, ssr, ssk);
+    return launch_status();
+}
+
+ds3_status launch_dequant_e5m6(const uint8_t* q, int64_t rows, int64_t cols, int64_t ldq, const float* s, int64_t ssr,
+                               int64_t ssk, void* y, int64_t ldy, hipStream_t st) {
+    const int64_t n = rows * (cols / 8);
+    dequant_e5m6_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(q, rows, cols, ldq, s, ssr, ssk, (uint8_t*)y, ldy * 2);
     return launch_status();
 }
 

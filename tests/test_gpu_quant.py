@@ -216,3 +216,35 @@ def test_rmsnorm_fused_with_quantizer(ds3, shape, pow2):
     # without the BF16 output the codes are the same
     q2, s2 = fn(dev(x, bf16=True), dev(gamma), 1e-6)
     assert torch.equal(q2, q) and torch.equal(s2, s)
+
+
+@pytest.mark.parametrize("shape", [(512, 7168), (33, 1160), (1, 128), (300, 200), (17, 8)])
+def test_e5m6_cache_quantizer_and_dequantizer(ds3, shape):
+    announce(f"e5m6 {shape}")
+    x = wl.cfg2_x(m=shape[0], k=shape[1])
+    x[0, : min(128, shape[1])] *= np.float32(2.0 ** -20)            # a tile deep in the subnormal-prone range of its neighbours
+    x = wl.bf16_round(x)
+    q, s = ds3.ds3_quant_act_1x128_e5m6(dev(x, bf16=True))
+    q_ref, s_ref = orc.quant_act_1x128_e5m6(x)
+    _cmp_codes_scales(q, s, q_ref, s_ref, "e5m6")
+    y = host(ds3.ds3_dequant_e5m6(q, s))
+    assert np.array_equal(y.astype(np.float64), orc.dequant_e5m6(q_ref, s_ref))
+
+
+def test_e5m6_device_rounding_on_every_code_and_tie(ds3):
+    """A tile whose max-abs is 65024 has scale 1: its other elements are converted as they are."""
+    announce("e5m6 rounding sweep")
+    codes = np.array([c for c in range(2048) if (c >> 6) != 31], dtype=np.uint16)
+    pos = orc.e5m6_decode(codes)
+    pts = np.concatenate([pos, (pos[:-1] + pos[1:]) / 2])
+    pts = np.concatenate([pts, np.nextafter(pts.astype(np.float32), np.float32(0)), np.nextafter(pts.astype(np.float32), np.float32(1e9))])
+    v = wl.bf16_round(pts.astype(np.float32))                        # the kernel takes BF16 input
+    v = np.unique(v[(v >= 0) & (v <= 65024)])
+    v = np.concatenate([v, -v])
+    pad = (-v.size) % 127
+    v = np.concatenate([v, np.zeros(pad, np.float32)]).reshape(-1, 127)
+    x = np.concatenate([np.full((v.shape[0], 1), 65024.0, np.float32), v], axis=1)
+    q, s = ds3.ds3_quant_act_1x128_e5m6(dev(x, bf16=True))
+    q_ref, s_ref = orc.quant_act_1x128_e5m6(x)
+    assert np.all(s_ref == 1.0)
+    _cmp_codes_scales(q, s, q_ref, s_ref, "e5m6 sweep")
