@@ -140,6 +140,44 @@ def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
     return step, kernels, 2.0 * M * N * K, cfg, "gemm_fp8_bs"
 
 
+def library_context(torch, dev, M=4096, N=18432, K=7168):
+    """Context only: what the vendor GEMM library reaches on this machine for the cfg2 shape WITHOUT block
+    scaling (one scale per tensor) and in BF16.  Nothing of the product runs through it."""
+    out = {}
+
+    def rate(fn):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.25:
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(50):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * M * N * K / (e0.elapsed_time(e1) / 50 * 1e-3) / 1e12
+
+    try:
+        a = torch.randn(M, K, device=dev).to(torch.float8_e4m3fn)
+        b = torch.randn(N, K, device=dev).to(torch.float8_e4m3fn)
+        one = torch.tensor(1.0, device=dev)
+        out["fp8_per_tensor_scale_gemm_tflops"] = rate(
+            lambda: torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16))
+        del a, b
+    except Exception as e:                       # the call is private API of the installed torch
+        out["fp8_per_tensor_scale_gemm_tflops"] = None
+        out["fp8_error"] = repr(e)[:120]
+    a = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+    b = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
+    out["bf16_gemm_tflops"] = rate(lambda: a @ b.t())
+    out["shape"] = [M, N, K]
+    return out
+
+
 def machine_probes(ds3, torch, dev):
     """What this chip sustains: FP8 MFMA rate from registers, and L2 -> LDS feed rate per compute unit."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
@@ -163,7 +201,8 @@ def machine_probes(ds3, torch, dev):
     mfma = cus * 8 * iters * 32 * 65536.0 / t / 1e12
     t = timed(lambda: ds3.ds3_probe_lds_feed(src, 7168, iters, cus, out_i))
     feed = iters * 65536.0 / t / 1e9
-    return {"mfma_fp8_register_loop_tflops": mfma, "mfma_fp8_register_loop_frac_of_peak": mfma / PEAK_FP8_TFLOPS,
+    lib = library_context(torch, dev)
+    return {"library_context": lib, "mfma_fp8_register_loop_tflops": mfma, "mfma_fp8_register_loop_frac_of_peak": mfma / PEAK_FP8_TFLOPS,
             "l2_to_lds_feed_gbs_per_cu": feed, "l2_to_lds_feed_tbs_total": feed * cus / 1e3,
             "feed_needed_gbs_per_cu_at_register_loop_rate": 65536.0 / (2.0 * 256 * 256 * 128 / (mfma * 1e12 / cus)) / 1e9,
             "note": "a 256x256 FP8 tile consumes 64 KiB of operands per 128-deep K-step (2*256*256*128 flop)"}
