@@ -529,14 +529,14 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 uint8_t* gp = c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ;
                 if (nl + 16 / ESZ <= cur.n_rows) {
                     if constexpr (OUT_BF16) {
-                        *reinterpret_cast<u32x4*>(gp) = w;
+                        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(gp));
                     } else {
                         f32x4 o = f32x4{as_f32(w.x), as_f32(w.y), as_f32(w.z), as_f32(w.w)};
                         if (accum) {
                             const f32x4 old = oldv[j & 1][ps];
                             o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
                         }
-                        *reinterpret_cast<f32x4*>(gp) = o;
+                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(gp));
                     }
                 } else {
                     const unsigned int wd[4] = {w.x, w.y, w.z, w.w};
