@@ -501,7 +501,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 const int nl = n_w0 + (idx % CPR) * (16 / ESZ);
                 dstv[ps] = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (ml < cur.m_rows && nl + 16 / ESZ <= cur.n_rows)
-                    dstv[ps] = *reinterpret_cast<const f32x4*>(c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ);
+                    dstv[ps] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ));
             }
         };
         const bool accum = !OUT_BF16 && p.accumulate;
