@@ -21,7 +21,7 @@ What it follows (DeepSeek-V3 technical report, arXiv 2412.19437):
 * Section 3.3.1: GEMM outputs are BF16 or FP32 (the oracle leaves its result
   unrounded in FP64; the comparison tolerance covers the output rounding).
 
-Readings where the paper is silent (all are repeated in the design notes):
+Readings where the paper is silent:
 
 * "maximum representable value of FP8" = 448, the OCP E4M3 maximum.
 * The stored factor is the de-quantisation scale  s = fl32(amax / 448).
