@@ -13,6 +13,14 @@
  *     interval and accumulates in FP32.
  *   - Section 3.3.1: Fprop, Dgrad and Wgrad take FP8 inputs and produce BF16
  *     or FP32 outputs.
+ * The five core calls (ds3_quant_act_1x128, ds3_quant_act_128x1,
+ * ds3_quant_w_128x128, ds3_gemm_fp8_bs, ds3_grouped_gemm_fp8_bs) come first;
+ * after them the pieces of Section 3.3.3 / 3.5.2 around the layer: SwiGLU,
+ * power-of-two scaling factors with the scales applied by the matrix
+ * instruction, the weight quantizer that also writes the transposed codes,
+ * re-tiling of the FP8 activation cache, SwiGLU and RMSNorm fused with their
+ * quantizer, the E5M6 cache format, the AdamW step with BF16 moments, and two
+ * machine probes for the benchmark.
  *
  * Common rules
  *   - Every data pointer is DEVICE memory owned by the caller.  The library
