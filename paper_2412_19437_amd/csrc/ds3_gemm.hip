@@ -486,7 +486,9 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         constexpr int PASSES = 16 * CPR / 64;              // 64 lanes move 16 rows x CPR chunks
         static_assert(16 * CPR % 64 == 0, "epilogue mapping");
         static_assert((NT / 64) * 16 * ROWB <= STAGE, "epilogue strips fit in one code stage");
-        uint8_t* strip = smem + (NS - 1) * STAGE + wave * (16 * ROWB);
+        // two strips per wave where they fit: the next row group is written while this one's reads return
+        constexpr int NSTRIP = (NT / 64) * 16 * ROWB * 2 <= STAGE ? 2 : 1;
+        uint8_t* strip0 = smem + (NS - 1) * STAGE + wave * (16 * ROWB * NSTRIP);
         uint8_t* c_base = reinterpret_cast<uint8_t*>(p.c);
         const int n_w0 = wn * C::TN;                       // first column of this wave inside the tile
         // Accumulating FP32 output: the old values of fragment row group j+1 are fetched
@@ -505,26 +507,32 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             }
         };
         const bool accum = !OUT_BF16 && p.accumulate;
-        if (active) {
-        if constexpr (!OUT_BF16) { if (accum) fetch_old(0, oldv[0]); }
-#pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            if constexpr (!OUT_BF16) { if (accum && j + 1 < FM) fetch_old(j + 1, oldv[(j + 1) & 1]); }
+        auto put_group = [&](int j) {                      // accumulators of row group j -> strip
+            uint8_t* sp = strip0 + (NSTRIP == 2 ? (j & 1) * (16 * ROWB) : 0);
 #pragma unroll
             for (int i = 0; i < FN; ++i) {
                 const f32x4 v = acc[i][j];
-                uint8_t* dst = strip + l16 * ROWB + (i * 16 + g4 * 4) * ESZ;
+                uint8_t* dst = sp + l16 * ROWB + (i * 16 + g4 * 4) * ESZ;
                 if constexpr (OUT_BF16) *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
                 else *reinterpret_cast<f32x4*>(dst) = v;
             }
-            __builtin_amdgcn_wave_barrier();               // same-wave LDS accesses complete in order
+        };
+        auto get_group = [&](int j, u32x4* wv) {           // strip -> 16-byte row chunks
+            const uint8_t* sp = strip0 + (NSTRIP == 2 ? (j & 1) * (16 * ROWB) : 0);
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int idx = ps * 64 + lane;
+                wv[ps] = *reinterpret_cast<const u32x4*>(sp + (idx / CPR) * ROWB + (idx % CPR) * 16);
+            }
+        };
+        auto store_group = [&](int j, const u32x4* wv) {
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
                 const int idx = ps * 64 + lane;
                 const int r = idx / CPR, ch = idx % CPR;
                 const int ml = wm * C::TM + j * 16 + r;
                 const int nl = n_w0 + ch * (16 / ESZ);     // first column of this chunk inside the tile
-                const u32x4 w = *reinterpret_cast<const u32x4*>(strip + r * ROWB + ch * 16);
+                const u32x4 w = wv[ps];
                 if (ml >= cur.m_rows || nl >= cur.n_rows) continue;
                 uint8_t* gp = c_base + ((int64_t)(cur.m0 + ml) * p.ldc + cur.n0 + nl) * ESZ;
                 if (nl + 16 / ESZ <= cur.n_rows) {
@@ -550,8 +558,23 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     }
                 }
             }
-            __builtin_amdgcn_wave_barrier();               // reads of the strip precede the next round of writes
-        }
+        };
+        if (active) {
+            if constexpr (!OUT_BF16) { if (accum) fetch_old(0, oldv[0]); }
+            put_group(0);
+#pragma unroll
+            for (int j = 0; j < FM; ++j) {
+                if constexpr (!OUT_BF16) { if (accum && j + 1 < FM) fetch_old(j + 1, oldv[(j + 1) & 1]); }
+                __builtin_amdgcn_wave_barrier();           // same-wave LDS accesses complete in order
+                u32x4 wv[PASSES];
+                get_group(j, wv);
+                if constexpr (NSTRIP == 2) { if (j + 1 < FM) put_group(j + 1); }
+                store_group(j, wv);
+                if constexpr (NSTRIP == 1) {
+                    __builtin_amdgcn_wave_barrier();       // reads of the strip precede the next round of writes
+                    if (j + 1 < FM) put_group(j + 1);
+                }
+            }
         }
         if (!more) break;
         cur = nxt;
