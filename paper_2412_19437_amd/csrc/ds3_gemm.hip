@@ -219,13 +219,14 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? c.rs_b : c.rs_a, (lds_ptr_t)dst, 16, (int)voff, 0, 0, 0);
     };
+    // only the waves whose thread index is a tile row take part (wave-uniform conditions)
     auto load_scales = [&](const TileCtx& c, int kb) { // global -> registers
-        sa_reg = c.sa_thr[(int64_t)kb * p.sak];
-        if constexpr (ROWSB) sbrow_reg = c.sbrow_thr[(int64_t)kb * p.sbk];
+        if (tid < BM) sa_reg = c.sa_thr[(int64_t)kb * p.sak];
+        if constexpr (ROWSB) { if (tid < BN) sbrow_reg = c.sbrow_thr[(int64_t)kb * p.sbk]; }
     };
     auto commit_scales = [&](int stage) {              // registers -> LDS
-        sa_s[stage * NT + tid] = sa_reg;
-        if constexpr (ROWSB) sbrow_s[stage * NT + tid] = sbrow_reg;
+        if (tid < BM) sa_s[stage * NT + tid] = sa_reg;
+        if constexpr (ROWSB) { if (tid < BN) sbrow_s[stage * NT + tid] = sbrow_reg; }
     };
     auto load_frag = [&](const uint8_t* base) -> i32x8 {
         const i32x4 lo = *reinterpret_cast<const i32x4*>(base + foff0);
