@@ -60,7 +60,8 @@ typedef enum {
     DS3_ERR_ALIGN = 3,       /* pointer / ld / column count not vector aligned   */
     DS3_ERR_DTYPE = 4,       /* unknown dtype, or accumulate into a BF16 output  */
     DS3_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (2^31 bytes per operand row span etc.) */
-    DS3_ERR_LAUNCH = 6       /* the HIP runtime refused the launch               */
+    DS3_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch               */
+    DS3_ERR_WORKSPACE = 7    /* a workspace was passed that is smaller than ds3_gemm_workspace_bytes asks for */
 } ds3_status;
 
 typedef enum { DS3_F32 = 0, DS3_BF16 = 1 } ds3_dtype;
@@ -128,10 +129,20 @@ ds3_status ds3_quant_w_128x128(const void* w, ds3_dtype wt, int64_t n, int64_t k
  *   Section 3.3.3 keeps gradients in FP32).
  * Requirements: K % 128 == 0; a, b 16-byte aligned and lda, ldb % 16 == 0;
  * c 16-byte aligned and ldc % 4 == 0.  M and N are arbitrary.
- * `workspace` is reserved for split-K variants; pass what
- * ds3_gemm_workspace_bytes() asks for (currently 0, NULL is accepted).
- * The order of the FP32 additions is unspecified (results are deterministic
- * for a given shape, but not bit-comparable across shapes).
+ * K == 0 is an empty sum: C is left as it is with `accumulate`, set to zero
+ * without.
+ * `workspace` (device memory, 16-byte aligned, owned by the caller, prepared
+ * once with ds3_gemm_workspace_init, must not be shared by calls that may run
+ * at the same time; every call leaves it ready for the next, whatever the shape): when
+ * the output tiles do not divide evenly among the compute units, the tiles of
+ * the last, partial round are shared along K -- every workgroup takes an
+ * equal run of their K-steps, partial sums meet in the workspace and are added
+ * in K order by whichever workgroup completes a tile (Section 3.3.2 leaves the
+ * order of the FP32 additions open).  Pass ds3_gemm_workspace_bytes() bytes to
+ * allow it, or NULL (with any size) to forbid it; a non-NULL workspace that is
+ * too small is DS3_ERR_WORKSPACE.  Results are deterministic for a given shape
+ * and workspace choice, but not bit-comparable across shapes or between a
+ * call with and a call without workspace.
  */
 ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K,
                            const uint8_t* a, int64_t lda,
@@ -231,8 +242,33 @@ ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* g
                                         void* c, ds3_dtype ct, int64_t ldc,
                                         void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of device workspace the GEMM calls need for this shape (0 today). */
+/*
+ * Bytes of device workspace with which ds3_gemm_fp8_bs / _pow2 share tail tiles
+ * along K for this shape (the larger of the two scale modes' needs; 0: the call
+ * would not use a workspace).  The _v form answers for one tile configuration
+ * and scale mode (variant -1: the default choice).  The grouped calls take no
+ * workspace (pass NULL).
+ */
 size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t ds3_gemm_workspace_bytes_v(int variant, int64_t M, int64_t N, int64_t K, ds3_bscale sb_mode);
+
+/*
+ * Prepares a freshly allocated workspace (enqueues a small kernel that zeroes
+ * the arrival counters at its head; the rest needs no initialisation).  Once
+ * per allocation: the GEMM calls leave the counters as they need them.
+ * workspace_bytes == 0 is a no-op; a non-zero size below the counters' 2 KiB is
+ * DS3_ERR_WORKSPACE.
+ */
+ds3_status ds3_gemm_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Host logic of the K-sharing, exported for its test (no GPU work): `tail_tiles`
+ * tiles of `k_steps` K-steps each, laid end to end, are cut into one contiguous
+ * run per workgroup, workgroup s taking steps [s*q, (s+1)*q).  Returns the
+ * smallest q >= ceil(tail_tiles * k_steps / workgroups) with which no tile is
+ * cut into more than two pieces, or 0 if only q = k_steps (no sharing) would do.
+ */
+int ds3_gemm_tail_share_steps(int tail_tiles, int k_steps, int workgroups);
 
 /*
  * SwiGLU between the two expert GEMMs (Section 3.3.3, Low-Precision

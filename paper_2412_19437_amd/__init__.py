@@ -24,7 +24,7 @@ DS3_BSCALE_128x128, DS3_BSCALE_PER_ROW = 0, 1
 SYMBOLS = [
     "ds3_quant_act_1x128", "ds3_quant_act_128x1", "ds3_quant_w_128x128",
     "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_gemm_fp8_bs_v", "ds3_grouped_gemm_fp8_bs_v",
-    "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_swiglu", "ds3_status_string",
+    "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_gemm_workspace_bytes_v", "ds3_gemm_tail_share_steps", "ds3_gemm_workspace_init", "ds3_swiglu", "ds3_status_string",
     "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
@@ -78,6 +78,11 @@ def _load() -> ctypes.CDLL:
     lib.ds3_gemm_num_variants.argtypes = []
     lib.ds3_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.ds3_gemm_workspace_bytes.restype = sz
+    lib.ds3_gemm_workspace_bytes_v.argtypes = [i32, i64, i64, i64, i32]
+    lib.ds3_gemm_workspace_bytes_v.restype = sz
+    lib.ds3_gemm_tail_share_steps.argtypes = [i32, i32, i32]
+    lib.ds3_gemm_workspace_init.argtypes = [vp, sz, vp]
+    lib.ds3_gemm_tail_share_steps.restype = i32
     lib.ds3_status_string.argtypes = [i32]
     lib.ds3_status_string.restype = ctypes.c_char_p
     for name in SYMBOLS:
@@ -205,20 +210,44 @@ def ds3_quant_w_128x128_pow2(w: torch.Tensor):
 
 
 def ds3_gemm_fp8_bs(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=torch.bfloat16,
-                    c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1):
+                    c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1, workspace="auto"):
     """C[M][N] (+)= block-scaled product of codes a [M][K] (scales sa, logical
     [M][K/128]) and b [N][K] (scales sb: [ceil(N/128)][K/128], or [N][K/128]
-    when sb_mode is DS3_BSCALE_PER_ROW)."""
-    return _gemm("ds3_gemm_fp8_bs_v", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant)
+    when sb_mode is DS3_BSCALE_PER_ROW).  workspace: "auto" (a cached tensor of the
+    size the library asks for), None (never share tiles along K) or a uint8 tensor."""
+    return _gemm("ds3_gemm_fp8_bs_v", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant, workspace)
 
 
 def ds3_gemm_fp8_bs_pow2(a, sa, b, sb, sb_mode: int = DS3_BSCALE_128x128, out_dtype=torch.bfloat16,
-                         c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1):
+                         c: torch.Tensor | None = None, accumulate: bool = False, variant: int = -1, workspace="auto"):
     """As ds3_gemm_fp8_bs for operands whose scales are all powers of two."""
-    return _gemm("ds3_gemm_fp8_bs_pow2", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant)
+    return _gemm("ds3_gemm_fp8_bs_pow2", a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant, workspace)
 
 
-def _gemm(entry, a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant):
+_workspaces: dict = {}
+
+
+def gemm_workspace(nbytes: int, device) -> torch.Tensor | None:
+    """A per-device, per-stream uint8 tensor of at least nbytes (None for 0), kept for reuse:
+    the GEMM's workspace must not be shared by calls that may overlap."""
+    if nbytes <= 0:
+        return None
+    key = (torch.device(device).index or 0, _stream())
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = new_gemm_workspace(nbytes, device)
+        _workspaces[key] = ws
+    return ws
+
+
+def new_gemm_workspace(nbytes: int, device) -> torch.Tensor:
+    """A uint8 tensor of nbytes, prepared with ds3_gemm_workspace_init on the current stream."""
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check(_L().ds3_gemm_workspace_init(ws.data_ptr(), nbytes, _stream()), "ds3_gemm_workspace_init")
+    return ws
+
+
+def _gemm(entry, a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant, workspace="auto"):
     m, k, lda = _rows2d(a, "a")
     n, kb_, ldb = _rows2d(b, "b")
     if kb_ != k:
@@ -226,9 +255,13 @@ def _gemm(entry, a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant):
     if c is None:
         c = _out(m, n, out_dtype, a.device)
     _, _, ldc = _rows2d(c, "c")
+    if isinstance(workspace, str):                 # "auto": what the library asks for, from the cache
+        workspace = gemm_workspace(_L().ds3_gemm_workspace_bytes_v(variant, m, n, k, sb_mode), a.device)
     st = getattr(_L(), entry)(variant, m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1),
                               b.data_ptr(), ldb, sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode,
-                              c.data_ptr(), _dt(c), ldc, int(accumulate), None, 0, _stream())
+                              c.data_ptr(), _dt(c), ldc, int(accumulate),
+                              workspace.data_ptr() if workspace is not None else None,
+                              workspace.numel() if workspace is not None else 0, _stream())
     _check(st, entry)
     return c
 
@@ -411,6 +444,10 @@ def ds3_gemm_num_variants() -> int:
 
 def ds3_gemm_workspace_bytes(m: int, n: int, k: int) -> int:
     return int(_L().ds3_gemm_workspace_bytes(m, n, k))
+
+
+def ds3_gemm_workspace_bytes_v(variant: int, m: int, n: int, k: int, sb_mode: int = DS3_BSCALE_128x128) -> int:
+    return int(_L().ds3_gemm_workspace_bytes_v(variant, m, n, k, sb_mode))
 
 
 def ds3_probe_mfma_fp8(iters: int, workgroups: int, out: torch.Tensor):

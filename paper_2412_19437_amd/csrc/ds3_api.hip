@@ -30,7 +30,7 @@ ds3_status check_quant(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, 
 ds3_status gemm_common(bool pow2, int variant, int32_t G, const int32_t* offs, int64_t M, int64_t N, int64_t K, const uint8_t* a,
                        int64_t lda, const float* sa, int64_t sar, int64_t sak, const uint8_t* b, int64_t ldb,
                        const float* sb, int64_t sbr, int64_t sbk, ds3_bscale mode, void* c, ds3_dtype ct, int64_t ldc,
-                       int accumulate, void* stream) {
+                       int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
     if (!dtype_ok(ct)) return DS3_ERR_DTYPE;
     if (mode != DS3_BSCALE_128x128 && mode != DS3_BSCALE_PER_ROW) return DS3_ERR_DTYPE;
     if (accumulate && ct != DS3_F32) return DS3_ERR_DTYPE;
@@ -38,13 +38,30 @@ ds3_status gemm_common(bool pow2, int variant, int32_t G, const int32_t* offs, i
     if (K % 128) return DS3_ERR_SHAPE;
     if (variant < -1 || variant >= gemm_num_variants()) return DS3_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return DS3_OK;
-    if (K == 0) return accumulate ? DS3_OK : DS3_ERR_SHAPE;   // an empty sum cannot overwrite C without a kernel
-    if (!a || !b || !sa || !sb || !c) return DS3_ERR_NULL;
-    if (G > 0 && !offs) return DS3_ERR_NULL;
-    if (lda < K || ldb < K || ldc < N) return DS3_ERR_SHAPE;
+    if (!c) return DS3_ERR_NULL;
+    if (ldc < N) return DS3_ERR_SHAPE;
+    if (!aligned16(c) || ldc % 4) return DS3_ERR_ALIGN;
     if (M > kMaxDim || N > kMaxDim || K > kMaxDim || G > 1023) return DS3_ERR_UNSUPPORTED;
-    if (!aligned16(a) || !aligned16(b) || !aligned16(c) || lda % 16 || ldb % 16 || ldc % 4) return DS3_ERR_ALIGN;
+    if (K == 0)                                               // an empty sum: C += 0, or C = 0
+        return accumulate ? DS3_OK : launch_zero_fill(c, ct, M, N, ldc, static_cast<hipStream_t>(stream));
+    if (!a || !b || !sa || !sb) return DS3_ERR_NULL;
+    if (G > 0 && !offs) return DS3_ERR_NULL;
+    if (lda < K || ldb < K) return DS3_ERR_SHAPE;
+    if (workspace && !aligned16(workspace)) return DS3_ERR_ALIGN;
+    if (!aligned16(a) || !aligned16(b) || lda % 16 || ldb % 16) return DS3_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DS3_ERR_ALIGN;
+    // the kernel addresses the scales with 31-bit byte offsets from sa / sb and non-negative strides
+    {
+        const int64_t kbm = K / 128, nb = mode == DS3_BSCALE_PER_ROW ? N : (N + 127) / 128, groups = G > 0 ? G : 1;
+        if (sar < 0 || sak < 0 || sbr < 0 || sbk < 0) return DS3_ERR_UNSUPPORTED;
+        const int64_t lim = (1ll << 29) - 1;       // elements
+        if ((M - 1) > lim / (sar > 0 ? sar : 1) || (kbm - 1) > lim / (sak > 0 ? sak : 1) ||
+            (M - 1) * sar + (kbm - 1) * sak > lim)
+            return DS3_ERR_UNSUPPORTED;
+        if ((nb - 1) > lim / (sbr > 0 ? sbr : 1) || (kbm - 1) > lim / (sbk > 0 ? sbk : 1) ||
+            (groups - 1) * ((N + 127) / 128) * kbm + (nb - 1) * sbr + (kbm - 1) * sbk > lim)
+            return DS3_ERR_UNSUPPORTED;
+    }
     GemmParams p{};
     p.a = a; p.b = b; p.sa = sa; p.sb = sb; p.c = c;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
@@ -54,18 +71,18 @@ ds3_status gemm_common(bool pow2, int variant, int32_t G, const int32_t* offs, i
     p.b_group_stride = N * ldb;
     p.sb_group_stride = ((N + 127) / 128) * (K / 128);
     p.accumulate = accumulate;
-    return launch_gemm(p, ct, mode, variant, pow2, static_cast<hipStream_t>(stream));
+    return launch_gemm(p, ct, mode, variant, pow2, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 ds3_status grouped_common(bool pow2, int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t N,
                           int64_t K, const uint8_t* a, int64_t lda, const float* sa, int64_t sar, int64_t sak,
                           const uint8_t* b, int64_t ldb, const float* sb, void* c, ds3_dtype ct, int64_t ldc,
-                          void* stream) {
+                          void* workspace, size_t workspace_bytes, void* stream) {
     if (G < 0) return DS3_ERR_SHAPE;
     if (G == 0) return DS3_OK;
     if (N > 0 && K > 0 && (int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
     return gemm_common(pow2, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sar, sak, b, ldb, sb, K / 128, 1,
-                       DS3_BSCALE_128x128, c, ct, ldc, 0, stream);
+                       DS3_BSCALE_128x128, c, ct, ldc, 0, workspace, workspace_bytes, stream);
 }
 
 }  // namespace
@@ -130,9 +147,8 @@ ds3_status ds3_gemm_fp8_bs_v(int variant, int64_t M, int64_t N, int64_t K, const
                              int64_t ldb, const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb,
                              ds3_bscale sb_mode, void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* workspace,
                              size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;
     return gemm_common(false, variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
-                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, stream);
+                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, workspace, workspace_bytes, stream);
 }
 
 ds3_status ds3_gemm_fp8_bs_pow2(int variant, int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda,
@@ -140,9 +156,8 @@ ds3_status ds3_gemm_fp8_bs_pow2(int variant, int64_t M, int64_t N, int64_t K, co
                                 int64_t ldb, const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb,
                                 ds3_bscale sb_mode, void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* workspace,
                                 size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;
     return gemm_common(true, variant, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb,
-                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, stream);
+                       sb_stride_row, sb_stride_kb, sb_mode, c, ct, ldc, accumulate, workspace, workspace_bytes, stream);
 }
 
 ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,
@@ -159,9 +174,8 @@ ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* grou
                                      int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
                                      const float* sb, void* c, ds3_dtype ct, int64_t ldc, void* workspace,
                                      size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;
     return grouped_common(false, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b,
-                          ldb, sb, c, ct, ldc, stream);
+                          ldb, sb, c, ct, ldc, workspace, workspace_bytes, stream);
 }
 
 ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
@@ -169,9 +183,8 @@ ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* g
                                         int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
                                         const float* sb, void* c, ds3_dtype ct, int64_t ldc, void* workspace,
                                         size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;
     return grouped_common(true, variant, G, group_offsets, total_rows, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b,
-                          ldb, sb, c, ct, ldc, stream);
+                          ldb, sb, c, ct, ldc, workspace, workspace_bytes, stream);
 }
 
 ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t N, int64_t K,
@@ -184,9 +197,30 @@ ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int6
 
 int ds3_gemm_num_variants(void) { return gemm_num_variants(); }
 
+size_t ds3_gemm_workspace_bytes_v(int variant, int64_t M, int64_t N, int64_t K, ds3_bscale sb_mode) {
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 || M > kMaxDim || N > kMaxDim || K > kMaxDim) return 0;
+    if (variant < -1 || variant >= gemm_num_variants()) return 0;
+    if (sb_mode != DS3_BSCALE_128x128 && sb_mode != DS3_BSCALE_PER_ROW) return 0;
+    GemmParams p{};
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    return gemm_workspace_bytes(p, sb_mode, variant);
+}
+
+ds3_status ds3_gemm_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace_bytes == 0) return DS3_OK;
+    if (!workspace) return DS3_ERR_NULL;
+    if (!aligned16(workspace)) return DS3_ERR_ALIGN;
+    return launch_workspace_init(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int ds3_gemm_tail_share_steps(int tail_tiles, int k_steps, int workgroups) {
+    return tail_share_steps(tail_tiles, k_steps, workgroups);
+}
+
 size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    (void)M; (void)N; (void)K;
-    return 0;
+    const size_t blk = ds3_gemm_workspace_bytes_v(-1, M, N, K, DS3_BSCALE_128x128);
+    const size_t row = ds3_gemm_workspace_bytes_v(-1, M, N, K, DS3_BSCALE_PER_ROW);
+    return blk > row ? blk : row;
 }
 
 ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh, void* out, int64_t ldo, void* stream) {
@@ -358,6 +392,7 @@ const char* ds3_status_string(ds3_status st) {
         case DS3_ERR_DTYPE: return "bad dtype / mode";
         case DS3_ERR_UNSUPPORTED: return "size or variant not supported";
         case DS3_ERR_LAUNCH: return "kernel launch failed";
+        case DS3_ERR_WORKSPACE: return "workspace smaller than ds3_gemm_workspace_bytes asks for";
     }
     return "unknown status";
 }

@@ -36,6 +36,10 @@ namespace ds3 {
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int kMaxGroups = 1023;                       // experts per grouped call (prefix table in LDS)
+constexpr int kShareSkew = 6;                          // K-steps by which the two pieces of a halved tile differ, each way
+constexpr int kAuxDevice = 16;                         // cache policy of a buffer access: sc1, coherent across the device
+constexpr int kTailCounters = 64;                      // arrival counters per XCD (tail tiles < workgroups per XCD <= 64)
+constexpr size_t kCounterBytes = 8 * kTailCounters * sizeof(int);
 
 template <int BN_, int BM_, int WN_, int WM_, int NS_>
 struct Cfg {
@@ -49,12 +53,9 @@ struct Cfg {
     static constexpr int STAGE = ROWS * 128;           // bytes of codes per K-step
     static constexpr int RPI = NT / 8;                 // tile rows one load instruction of the workgroup covers
     static constexpr int LPT = ROWS / RPI;             // 16-byte loads per thread per K-step
-#ifndef DS3_TAIL_LOADS
-#define DS3_TAIL_LOADS (LPT < FN ? LPT : FN)
-#endif
     // loads of a K-step that are issued right behind the barrier that frees their stage (the
     // rest go out at the head of the next K-step)
-    static constexpr int TAILN = (DS3_TAIL_LOADS) < LPT ? (DS3_TAIL_LOADS) : LPT;
+    static constexpr int TAILN = LPT < FN ? LPT : FN;
     static constexpr int SCALE_BYTES = 2 * NS * NT * 4;        // [NS][NT] sa + [NS][NT] per-row sb
     static constexpr int LDS_BYTES = NS * STAGE + SCALE_BYTES + (kMaxGroups + 1) * 4;   // + row-tile prefix of the experts
     // workgroups that fit one compute unit: 160 KiB of LDS, and two waves per SIMD (the
@@ -69,6 +70,16 @@ struct Cfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
+// Whether `tail` tiles left over after `rounds` full rounds on `nslots` workgroups are shared
+// along K.  Sharing costs about a sixth of a tile's time (partial sums through memory), so it
+// pays when the workgroups would otherwise idle for much longer: few tiles in all (no full
+// round: up to 0.6 tiles per workgroup), or a small remainder (up to a third; up to a half the
+// half-tile split does as well without a workspace).  Host and kernel use the same rule.
+__host__ __device__ inline bool tail_worth_sharing(int rounds, int tail, int nslots) {
+    if (tail <= 0) return false;
+    return rounds == 0 ? 5 * tail <= 3 * nslots : 3 * tail <= nslots;
+}
+
 // XOR key of a tile row: depends on the row's position inside its 16-row fragment only.
 __device__ __forceinline__ int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
@@ -80,10 +91,9 @@ constexpr unsigned kOobOffset = 0x80000000u;
 // except the two per-thread scale pointers).
 struct TileCtx {
     int m0, n0, m_rows, n_rows;
+    int kb0, kb1;             // K-steps [kb0, kb1) of the tile that this unit of work covers
     __amdgpu_buffer_rsrc_t rs_a, rs_b;
-    const float* sb_blk;      // block mode: this wave's block row of scales; row mode: tile base
-    const float* sa_thr;      // this thread's activation-scale row
-    const float* sbrow_thr;   // this thread's weight-scale row (per-row mode)
+    unsigned sc_off;          // byte offset of the row of scales this thread fetches one value of per K-step (see `scale_role`)
 };
 
 //
@@ -129,19 +139,83 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int ntiles = tiles_m * p.tiles_n;
     const int per_xcd = (ntiles + 7) >> 3;
     const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslots = (int)(gridDim.x >> 3);
-    // A last round that would occupy at most half of the XCD's workgroups is cut into
-    // half tiles (the two M halves of a tile belong to different waves, and the waves
-    // of the missing half skip their MFMAs), so that every workgroup gets one.
-    const int tail = per_xcd % nslots;
-    const bool split_tail = !GROUPED && C::WM == 2 && per_xcd > nslots && tail > 0 && 2 * tail <= nslots && p.M % BM == 0;
-    const int n_full = split_tail ? per_xcd - tail : per_xcd;
-    const int n_virtual = split_tail ? n_full + 2 * tail : per_xcd;
+    // The XCD's tiles are taken in rounds of one tile per workgroup.  What is left
+    // after the last full round (`tail` tiles, fewer than workgroups) is either
+    //  * shared along K: the tail's K-steps, tile after tile, are cut into equal
+    //    contiguous ranges, one per workgroup; a workgroup's range touches at most two
+    //    tiles (its pieces), every piece's partial sums meet in the workspace and the
+    //    workgroup that finishes a tile's last piece adds them up in piece order and
+    //    writes the output -- nobody ever waits for another workgroup; or
+    //  * (no workspace) cut into half tiles when at most half of the workgroups would
+    //    get one: the two M halves of a tile belong to different waves, and the waves
+    //    of the missing half skip their MFMAs.
+    // The walk's geometry is needed only between tiles; the dense kernels keep it in LDS
+    // rather than in scalar registers across the K-loop.
+    struct Walk { int rounds, tail, mode, q, ra, rb, pt0, pt1, n_units, tail_steps; };
+    enum { kWhole = 0, kShareK = 1, kHalfTiles = 2 };
+    auto compute_walk = [&]() -> Walk {
+        Walk w;
+        const int cnt_x = max(0, min(per_xcd, ntiles - xcd * per_xcd));
+        w.rounds = cnt_x / nslots;
+        w.tail = cnt_x - w.rounds * nslots;
+        const bool share_k = !GROUPED && p.ws_cnt != nullptr && tail_worth_sharing(w.rounds, w.tail, nslots) &&
+                             (cnt_x == per_xcd ? p.share_steps : p.share_steps_last) > 0;
+        const bool halves = !share_k && !GROUPED && C::WM == 2 && w.rounds > 0 && w.tail > 0 && 2 * w.tail <= nslots && p.M % BM == 0;
+        w.mode = share_k ? kShareK : (halves ? kHalfTiles : kWhole);
+        w.tail_steps = w.tail * KB;
+        // K-steps per workgroup: the host's choice (an equal share, raised until no tile is cut
+        // into more than two pieces); the last XCD's chunk may be shorter and has its own
+        w.q = share_k ? (cnt_x == per_xcd ? p.share_steps : p.share_steps_last) : 1;
+        // (p.share_skew lengthens the even runs and shortens the odd ones when every tile is cut
+        // exactly in the middle: the shorter piece is then stored while the longer one still
+        // computes, and only one of the two is ever written)
+        const int skew = p.share_skew;
+        w.ra = share_k ? min(slot * w.q + ((slot & 1) ? skew : 0), w.tail_steps) : 0;
+        w.rb = share_k ? min((slot + 1) * w.q + ((slot & 1) ? 0 : skew), w.tail_steps) : 0;
+        w.pt0 = w.ra / KB;                                   // tail tile of the first piece
+        w.pt1 = w.rb > w.ra ? (w.rb - 1) / KB : w.pt0;       // tail tile of the last piece
+        const int n_tail_units = share_k ? (w.rb > w.ra ? 1 + (w.pt1 > w.pt0 ? 1 : 0) : 0)
+                                         : (halves ? (slot < 2 * w.tail ? 1 : 0) : (slot < w.tail ? 1 : 0));
+        w.n_units = w.rounds + n_tail_units;
+        return w;
+    };
+    // Dense kernels keep the three numbers every unit needs in registers and the geometry of a
+    // shared tail in LDS (the prefix table's space is free there), read when a tail unit comes up.
+    int* const walk_s = gpre + 4;
+    int w_rounds, w_mode, w_units;
+    {
+        const Walk w = compute_walk();
+        w_rounds = w.rounds; w_mode = w.mode; w_units = w.n_units;
+        if constexpr (!GROUPED) {
+            if (tid == 0) {
+                walk_s[0] = w.q; walk_s[1] = w.ra; walk_s[2] = w.rb; walk_s[3] = w.pt0; walk_s[4] = w.pt1; walk_s[5] = w.tail_steps;
+            }
+            __syncthreads();
+        }
+    }
+    struct Tail { int q, ra, rb, pt0, pt1, tail_steps; };
+    auto load_tail = [&]() -> Tail {
+        Tail w;
+        asm volatile("" ::: "memory");
+        auto rd = [&](int i) { return __builtin_amdgcn_readfirstlane(walk_s[i]); };
+        w.q = rd(0); w.ra = rd(1); w.rb = rd(2); w.pt0 = rd(3); w.pt1 = rd(4); w.tail_steps = rd(5);
+        return w;
+    };
 
-    auto setup_tile = [&](int local, TileCtx& c) -> bool {
-        if (local >= n_virtual) return false;
-        const int half = local < n_full ? -1 : ((local - n_full) & 1);
-        const int t = xcd * per_xcd + (local < n_full ? local : n_full + ((local - n_full) >> 1));
-        if (t >= ntiles) return false;
+    auto setup_unit = [&](int u, TileCtx& c) -> bool {
+        if (u >= w_units) return false;
+        int half = -1, local;                          // local: index of the tile inside the XCD's chunk
+        c.kb0 = 0; c.kb1 = KB;
+        if (u < w_rounds) local = u * nslots + slot;
+        else if (!GROUPED && w_mode == kShareK) {
+            const Tail w = load_tail();
+            const int tt = u == w_rounds ? w.pt0 : w.pt1;   // first / second piece of this workgroup
+            local = w_rounds * nslots + tt;
+            c.kb0 = max(w.ra - tt * KB, 0);
+            c.kb1 = min(w.rb - tt * KB, KB);
+        } else if (w_mode == kHalfTiles) { half = slot & 1; local = w_rounds * nslots + (slot >> 1); }
+        else local = w_rounds * nslots + slot;
+        const int t = xcd * per_xcd + local;
         int m0, m_end, n0, grp = 0;
         if constexpr (!GROUPED) {
             constexpr int PM = 4;                      // tiles of M per panel
@@ -180,18 +254,19 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         // expert's group) read as zero and touch no memory.
         c.rs_a = __builtin_amdgcn_make_buffer_rsrc((void*)a_tile, 0, (int)((int64_t)(c.m_rows - 1) * p.lda + p.K), 0x00020000);
         c.rs_b = __builtin_amdgcn_make_buffer_rsrc((void*)b_tile, 0, (int)((int64_t)(c.n_rows - 1) * p.ldb + p.K), 0x00020000);
-        if constexpr (ROWSB) {
-            c.sb_blk = p.sb + (int64_t)n0 * p.sbr;
-        } else {
+        // Every K-step a thread fetches at most one scale, straight into LDS: the first BM
+        // threads their activation row's; in block mode the lanes of the next wave the
+        // weight-block scale of wave column min(lane, WN - 1); in per-row mode the last BN
+        // threads their weight row's.  Rows past the valid ones repeat the last valid row,
+        // whose partial sums are zero because its codes were read as zero.
+        // (offsets from p.sa / p.sb in bytes; the host has checked that they fit 31 bits)
+        if (tid < BM) c.sc_off = (unsigned)((m0 + min(tid, c.m_rows - 1)) * (int)p.sar) * 4u;
+        else if constexpr (ROWSB) c.sc_off = (unsigned)((n0 + min(max(tid - (NT - BN), 0), c.n_rows - 1)) * (int)p.sbr) * 4u;
+        else {
             const int nblocks = (p.N + 127) >> 7;
-            const int nb = min((n0 + wn * C::TN) >> 7, nblocks - 1);
-            c.sb_blk = p.sb + (int64_t)grp * p.sb_group_stride + (int64_t)nb * p.sbr;
+            const int nb = min((n0 + min(lane, C::WN - 1) * C::TN) >> 7, nblocks - 1);
+            c.sc_off = (unsigned)(grp * (int)p.sb_group_stride + nb * (int)p.sbr) * 4u;
         }
-        // Every thread stages one activation scale (and one per-row weight scale);
-        // threads past the valid rows re-read the last valid row, whose partial
-        // sums are zero because its codes were read as zero.
-        c.sa_thr = p.sa + ((int64_t)m0 + min(tid, c.m_rows - 1)) * p.sar;
-        c.sbrow_thr = ROWSB ? c.sb_blk + (int64_t)min(tid, c.n_rows - 1) * p.sbr : nullptr;
         return true;
     };
 
@@ -209,31 +284,50 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int p_base = wn * C::TN * 128;               // weight fragments of this wave
     const int q_base = (BN + wm * C::TM) * 128;        // activation fragments of this wave
 
-    float sa_reg = 0.f, sbrow_reg = 0.f;
+    // which scale this wave fetches (wave-uniform): 0 none, 1 activation rows, 2 weight scales
+    const int scale_role = wave * 64 < BM ? 1 : ((ROWSB ? wave * 64 >= NT - BN : wave * 64 == BM) ? 2 : 0);
+    static_assert(ROWSB ? BM + BN <= NT : BM + 64 <= NT, "one scale per thread and K-step");
+    // Bytes between the scales of consecutive K-steps in the row this thread fetches from.  Kept
+    // in a vector register: as a scalar it would be re-read from the kernel arguments inside the
+    // K-loop, and a scalar load in flight turns every counted wait for LDS data into a full one.
+    unsigned sc_kstride = (unsigned)(scale_role == 1 ? (int)p.sak : (int)p.sbk) * 4u;
+    asm volatile("" : "+v"(sc_kstride));
+    // one descriptor over the activation or the weight scales, whichever this wave fetches (every
+    // offset it is used with is valid; the range check is not relied on)
+    const __amdgpu_buffer_rsrc_t rs_sc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(scale_role == 1 ? p.sa : p.sb), 0, 0x7ffffffc, 0x00020000);
 
     // i-th 16-byte load of this thread for the K-step at byte offset koff, into LDS stage `stage`
     auto issue_load = [&](const TileCtx& c, int i, int stage, unsigned koff) {
         const bool is_b = i * C::RPI < BN;
         const int ii = is_b ? i : i - BN / C::RPI;
-        const unsigned voff = (is_b ? voff_b : voff_a) + (koff + (unsigned)ii * (is_b ? step_b : step_a));
+        // the wave-uniform part of the offset is summed in a scalar register and added last (tied to
+        // a scalar register here so that it is not folded into eight per-load vector registers)
+        unsigned uoff = koff + (unsigned)ii * (is_b ? step_b : step_a);
+        asm volatile("" : "+s"(uoff));
+        const unsigned voff = (is_b ? voff_b : voff_a) + uoff;
         uint8_t* dst = smem + stage * STAGE + (i * NT + wave * 64) * 16;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(is_b ? c.rs_b : c.rs_a, (lds_ptr_t)dst, 16, (int)voff, 0, 0, 0);
     };
-    // only the waves whose thread index is a tile row take part (wave-uniform conditions)
-    auto load_scales = [&](const TileCtx& c, int kb) { // global -> registers
-        if (tid < BM) sa_reg = c.sa_thr[(int64_t)kb * p.sak];
-        if constexpr (ROWSB) { if (tid < BN) sbrow_reg = c.sbrow_thr[(int64_t)kb * p.sbk]; }
-    };
-    auto commit_scales = [&](int stage) {              // registers -> LDS
-        if (tid < BM) sa_s[stage * NT + tid] = sa_reg;
-        if constexpr (ROWSB) { if (tid < BN) sbrow_s[stage * NT + tid] = sbrow_reg; }
+    // The scales of K-step kb (clamped to the unit's last) go global -> LDS like the codes, into
+    // staging slot `stage`: activation scales at sa_s[stage][row], block scales behind them at
+    // sa_s[stage][BM + wave column], per-row weight scales at sbrow_s[stage][row].
+    auto issue_scale = [&](const TileCtx& c, int kb, int stage) {
+        if (scale_role == 0) return;
+        const int kc = min(kb, c.kb1 - 1);
+        float* dst = (ROWSB && scale_role == 2) ? sbrow_s + stage * NT + (wave * 64 - (NT - BN)) : sa_s + stage * NT + wave * 64;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_sc, (lds_ptr_t)dst, 4, (int)(c.sc_off + (unsigned)kc * sc_kstride), 0, 0, 0);
     };
     auto load_frag = [&](const uint8_t* base) -> i32x8 {
         const i32x4 lo = *reinterpret_cast<const i32x4*>(base + foff0);
         const i32x4 hi = *reinterpret_cast<const i32x4*>(base + foff1);
         return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     };
-    auto read_tj = [&](int stage, float sbv, float* tj) {
+    auto read_sb = [&](int stage) -> float {           // this wave's weight-block scale (block mode)
+        return sa_s[stage * NT + BM + wn];
+    };
+    auto read_tj = [&](int stage, float* tj) {
+        [[maybe_unused]] const float sbv = (ROWSB || POW2) ? 1.f : read_sb(stage);
 #pragma unroll
         for (int j = 0; j < FM; ++j) {
             const float sav = sa_s[stage * NT + wm * C::TM + j * 16 + l16];
@@ -242,8 +336,8 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     };
 
     TileCtx cur;
-    int local = slot;
-    if (!setup_tile(local, cur)) return;
+    int unit = 0;
+    if (!setup_unit(unit, cur)) return;
     // Workgroup barrier that lets the newest `pending` vector-memory operations of this
     // wave stay in flight (the loads that run more than one K-step ahead); LDS
     // operations are all complete when it returns.
@@ -255,28 +349,37 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
+    // The barrier of a K-step: the loads issued since the previous one -- LPT of codes, and one
+    // of scales in the waves that fetch any -- run a K-step further ahead when there are three
+    // stages and may stay in flight.
+    auto kstep_barrier = [&]() {
+        if constexpr (NS == 2) barrier_keep(std::integral_constant<int, 0>{});
+        else if (scale_role != 0) barrier_keep(std::integral_constant<int, C::LPT + 1>{});
+        else barrier_keep(std::integral_constant<int, C::LPT>{});
+    };
     // the first NS-1 K-steps of the first tile into stages 0 .. NS-2
     auto issue_first_steps = [&](const TileCtx& c) {
 #pragma unroll
-        for (int ks = 0; ks < NS - 1; ++ks)
+        for (int ks = 0; ks < NS - 1; ++ks) {
 #pragma unroll
-            for (int i = 0; i < C::LPT; ++i) issue_load(c, i, ks, ks < KB ? (unsigned)ks << 7 : kOobOffset);
-        load_scales(c, 0);
+            for (int i = 0; i < C::LPT; ++i) issue_load(c, i, ks, c.kb0 + ks < c.kb1 ? (unsigned)(c.kb0 + ks) << 7 : kOobOffset);
+            issue_scale(c, c.kb0 + ks, ks);
+        }
     };
     issue_first_steps(cur);
 
     for (;;) {
-        // ---- entry: K-steps 0 .. NS-2 of `cur` are in flight into stages 0 .. NS-2, the scales of K-step 0 are in registers ----
-        commit_scales(0);
+        // ---- entry: K-steps 0 .. NS-2 of `cur` (codes and scales) are in flight into stages 0 .. NS-2 ----
         __syncthreads();
         // the part of K-step NS-1 that a previous K-step's barrier would have issued
 #pragma unroll
         for (int i = 0; i < C::TAILN; ++i)
-            issue_load(cur, i, NS - 1, NS - 1 < KB ? (unsigned)(NS - 1) << 7 : kOobOffset);
-        float sb_n = ROWSB ? 1.f : cur.sb_blk[(int64_t)min(1, KB - 1) * p.sbk];   // block scale of the NEXT K-step
+            issue_load(cur, i, NS - 1, cur.kb0 + NS - 1 < cur.kb1 ? (unsigned)(cur.kb0 + NS - 1) << 7 : kOobOffset);
+        issue_scale(cur, cur.kb0 + NS - 1, NS - 1);
+        const int KE = cur.kb1;                            // end of this unit's K-steps
         float tj[FM];
-        [[maybe_unused]] float sb_c = ROWSB ? 1.f : cur.sb_blk[0];                  // block scale of THIS K-step (POW2 only)
-        read_tj(0, sb_c, tj);
+        [[maybe_unused]] float sb_c = (POW2 && !ROWSB) ? read_sb(0) : 1.f;   // block scale of THIS K-step (POW2 only)
+        read_tj(0, tj);
         i32x8 pf[FN], qf[2];
 #pragma unroll
         for (int i = 0; i < FN; ++i) pf[i] = load_frag(smem + p_base + i * 2048);
@@ -316,17 +419,15 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 #pragma unroll
             for (int d = 0; d <= D; ++d) part[d] = f32x4{0.f, 0.f, 0.f, 0.f};
             float tjn[FM];                                  // scale products of the next K-step
-            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;   // head loads
-            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;           // tail loads
-            load_scales(cur, min(kb + 1, KB - 1));
+            const unsigned koff1 = kb + NS - 1 < KE ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;   // head loads
+            const unsigned koff2 = kb + NS < KE ? (unsigned)(kb + NS) << 7 : kOobOffset;           // tail loads
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < NSUB + D; ++s) {
                 if (s == NSUB - FN) {
                     // Everything this wave reads from stage S is in registers.  After the
                     // barrier the next stage is complete and stage S may be overwritten.
-                    commit_scales(SN);
-                    barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
+                    kstep_barrier();
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (s < HEADN) issue_load(cur, TAILN + s, SL, koff1);
@@ -340,10 +441,10 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                         pf[i] = load_frag(nst + p_base + i * 2048);
 #pragma unroll
                         for (int l = i; l < TAILN; l += FN) issue_load(cur, l, S, koff2);
+                        if (i == 0) issue_scale(cur, kb + NS, S);
                         if (i == FN - 1) {
                             qf[0] = load_frag(nst + q_base);
-                            read_tj(SN, sb_n, tjn);
-                            if constexpr (!ROWSB) sb_n = cur.sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
+                            read_tj(SN, tjn);
                         }
                     }
                 }
@@ -388,15 +489,13 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             for (int j = 0; j < FM; ++j) eb[j] = (int)(as_u32(tj[j]) >> 23);
             float tjn[FM];
             float sb_cn = sb_c;
-            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
-            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;
-            load_scales(cur, min(kb + 1, KB - 1));
+            const unsigned koff1 = kb + NS - 1 < KE ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
+            const unsigned koff2 = kb + NS < KE ? (unsigned)(kb + NS) << 7 : kOobOffset;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < NSUB; ++s) {
                 if (s == NSUB - FN) {
-                    commit_scales(SN);
-                    barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
+                    kstep_barrier();
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (s < HEADN) issue_load(cur, TAILN + s, SL, koff1);
@@ -408,13 +507,11 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     pf[i] = load_frag(nst + p_base + i * 2048);
 #pragma unroll
                     for (int l = i; l < TAILN; l += FN) issue_load(cur, l, S, koff2);
+                    if (i == 0) issue_scale(cur, kb + NS, S);
                     if (i == FN - 1) {
                         qf[0] = load_frag(nst + q_base);
-                        read_tj(SN, 1.f, tjn);
-                        if constexpr (!ROWSB) {
-                            sb_cn = sb_n;
-                            sb_n = cur.sb_blk[(int64_t)min(kb + 2, KB - 1) * p.sbk];
-                        }
+                        read_tj(SN, tjn);
+                        if constexpr (!ROWSB) sb_cn = read_sb(SN);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -430,15 +527,14 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         auto kstep_idle = [&](int kb, auto stage_tag) {
             constexpr int S = decltype(stage_tag)::value;
             constexpr int SN = (S + 1) % NS, SL = (S + NS - 1) % NS;
-            const unsigned koff1 = kb + NS - 1 < KB ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
-            const unsigned koff2 = kb + NS < KB ? (unsigned)(kb + NS) << 7 : kOobOffset;
-            load_scales(cur, min(kb + 1, KB - 1));
+            const unsigned koff1 = kb + NS - 1 < KE ? (unsigned)(kb + NS - 1) << 7 : kOobOffset;
+            const unsigned koff2 = kb + NS < KE ? (unsigned)(kb + NS) << 7 : kOobOffset;
 #pragma unroll
             for (int i = 0; i < HEADN; ++i) issue_load(cur, TAILN + i, SL, koff1);
-            commit_scales(SN);
-            barrier_keep(std::integral_constant<int, (NS == 2 ? 0 : C::LPT)>{});
+            kstep_barrier();
 #pragma unroll
             for (int i = 0; i < TAILN; ++i) issue_load(cur, i, S, koff2);
+            issue_scale(cur, kb + NS, S);
         };
 
         using st0 = std::integral_constant<int, 0>;
@@ -446,21 +542,21 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         using st2 = std::integral_constant<int, 2>;
         const bool active = wm * C::TM < cur.m_rows;    // wave-uniform
         auto kloop = [&](auto step) {
-            int kb = 0;
+            int kb = cur.kb0;
             if constexpr (NS == 2) {
-                for (; kb + 1 < KB; kb += 2) {
+                for (; kb + 1 < KE; kb += 2) {
                     step(kb, st0{});
                     step(kb + 1, st1{});
                 }
-                if (kb < KB) step(kb, st0{});
+                if (kb < KE) step(kb, st0{});
             } else {
-                for (; kb + 2 < KB; kb += 3) {
+                for (; kb + 2 < KE; kb += 3) {
                     step(kb, st0{});
                     step(kb + 1, st1{});
                     step(kb + 2, st2{});
                 }
-                if (kb < KB) step(kb, st0{});
-                if (kb + 1 < KB) step(kb + 1, st1{});
+                if (kb < KE) step(kb, st0{});
+                if (kb + 1 < KE) step(kb + 1, st1{});
             }
         };
         if (!active) kloop(kstep_idle);
@@ -469,10 +565,86 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         __syncthreads();                               // every wave is done with all code stages
 
         // ---- the next tile's first K-steps fly into stages 0 .. NS-2 during this tile's epilogue ----
+        // (what is read from LDS here is read before those loads are issued: the compiler makes an
+        // LDS read that follows LDS-bound loads wait for them)
+        [[maybe_unused]] int pieces = 1, my_part = 0, tail_tile = 0, first_slot = 0, share_q = 1, tail_steps = 0;
+        if constexpr (!GROUPED) {
+            if (w_mode == kShareK && unit >= w_rounds) {
+                const Tail w = load_tail();
+                share_q = w.q; tail_steps = w.tail_steps;
+                my_part = unit - w_rounds;                 // 0 / 1: first / second piece of this workgroup
+                tail_tile = my_part == 0 ? w.pt0 : w.pt1;
+                first_slot = (tail_tile * KB) / share_q;   // workgroup slot of the tile's first piece
+                pieces = ((tail_tile + 1) * KB - 1) / share_q - first_slot + 1;
+            }
+        }
         TileCtx nxt;
-        local += nslots;
-        const bool more = setup_tile(local, nxt);
+        ++unit;
+        const bool more = setup_unit(unit, nxt);
         if (more) issue_first_steps(nxt);
+
+        // ---- a piece of a tile that is shared along K -----------------------------------
+        // A shared tile has exactly two pieces.  The workgroup that finishes first stores its
+        // partial sums in the workspace, lane by lane; the one whose arrival completes the
+        // tile adds them to its own (a + b = b + a: the result does not depend on who is last)
+        // and goes on to the epilogue.
+        // Coherence without cache-wide operations: the partial sums are written and read
+        // with device-scope accesses (sc1: written through, read past this XCD's L2), the
+        // arrival counter is a device-scope atomic, and the order "sums before arrival" /
+        // "arrival before sums" is kept by waiting for the stores and by the barriers.  A
+        // device-scope fence would write back and invalidate the whole L2 under the
+        // workgroups that are still computing.
+        [[maybe_unused]] bool reduce = false;              // this unit completes a tile whose other piece waits in the workspace
+        [[maybe_unused]] __amdgpu_buffer_rsrc_t rs_other = cur.rs_a;
+        [[maybe_unused]] const int toff = tid * 16;
+        if constexpr (!GROUPED) {
+            const int q = share_q;
+            if (pieces > 1) {
+                constexpr int TILE_F = BN * BM;            // floats of one partial tile
+                int* const cnt = p.ws_cnt + xcd * kTailCounters + tail_tile;
+                // A partial tile is stored lane by lane: accumulator (i, j) of thread t at float
+                // ((i * FM + j) * NT + t) * 4.  Buffer addressing keeps the per-thread part of
+                // every address in one register (the accumulators leave few to spare).
+                auto part_rsrc = [&](int wg_slot, int which) {
+                    float* base = p.ws_part + (int64_t)((wg_slot * 8 + xcd) * 2 + which) * TILE_F;
+                    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, TILE_F * 4, 0x00020000);
+                };
+                auto part_of = [&](int k) {                // partial tile of the tile's k-th piece
+                    const int s2 = first_slot + k;
+                    return part_rsrc(s2, (min(s2 * q, tail_steps) / KB == tail_tile) ? 0 : 1);
+                };
+                auto store_mine = [&]() {
+                    const __amdgpu_buffer_rsrc_t rs = part_rsrc(slot, my_part);
+#pragma unroll
+                    for (int i = 0; i < FN; ++i)
+#pragma unroll
+                        for (int j = 0; j < FM; ++j) {
+                            const f32x4 v = acc[i][j];
+                            __builtin_amdgcn_raw_buffer_store_b128(u32x4{as_u32(v.x), as_u32(v.y), as_u32(v.z), as_u32(v.w)}, rs, toff,
+                                                                   (i * FM + j) * NT * 16, kAuxDevice);
+                        }
+                };
+                // has the other piece arrived already?  then this one need not be stored
+                if (tid == 0) gpre[0] = __hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                const bool others_done = (gpre[0] & 1) != 0;
+                __syncthreads();
+                if (!others_done) store_mine();
+                __builtin_amdgcn_s_waitcnt(0x0070);        // vmcnt(0): my partial sums have been written through
+                __syncthreads();                           // ... and everybody else's of this workgroup
+                if (tid == 0) gpre[0] = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                const bool last = (gpre[0] & 1) != 0;      // a tile's two arrivals take its counter from even to odd to even
+                __syncthreads();
+                if (!last) {
+                    if (!more) break;
+                    cur = nxt;
+                    continue;
+                }
+                reduce = true;                             // the epilogue adds the other piece in on its way out
+                rs_other = part_of(1 - (slot - first_slot));
+            }
+        }
 
         // ---- epilogue ------------------------------------------------------------------
         // A lane owns one activation row m and, per weight fragment, 4 consecutive n:
@@ -508,11 +680,26 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             }
         };
         const bool accum = !OUT_BF16 && p.accumulate;
-        auto put_group = [&](int j) {                      // accumulators of row group j -> strip
+        // The other piece's partial sums of row group j (a shared tile's second arrival only),
+        // fetched one group ahead of their use.
+        [[maybe_unused]] u32x4 otherv[2][FN];
+        auto fetch_other = [&](int j) {
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+                otherv[j & 1][i] = __builtin_amdgcn_raw_buffer_load_b128(rs_other, toff, (i * FM + j) * NT * 16, kAuxDevice);
+        };
+        // RED (compile time): this is the second arrival at a shared tile, the other piece is added in
+        auto put_group = [&](int j, auto red_tag) {        // accumulators of row group j -> strip
+            constexpr bool RED = decltype(red_tag)::value;
             uint8_t* sp = strip0 + (NSTRIP == 2 ? (j & 1) * (16 * ROWB) : 0);
+            if constexpr (RED) { if (j + 1 < FM) fetch_other(j + 1); }
 #pragma unroll
             for (int i = 0; i < FN; ++i) {
-                const f32x4 v = acc[i][j];
+                f32x4 v = acc[i][j];
+                if constexpr (RED) {
+                    const u32x4 o = otherv[j & 1][i];
+                    v.x += as_f32(o.x); v.y += as_f32(o.y); v.z += as_f32(o.z); v.w += as_f32(o.w);
+                }
                 uint8_t* dst = sp + l16 * ROWB + (i * 16 + g4 * 4) * ESZ;
                 if constexpr (OUT_BF16) *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
                 else *reinterpret_cast<f32x4*>(dst) = v;
@@ -560,22 +747,28 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 }
             }
         };
-        if (active) {
+        auto write_out = [&](auto red_tag) {
             if constexpr (!OUT_BF16) { if (accum) fetch_old(0, oldv[0]); }
-            put_group(0);
+            if constexpr (decltype(red_tag)::value) fetch_other(0);
+            put_group(0, red_tag);
 #pragma unroll
             for (int j = 0; j < FM; ++j) {
                 if constexpr (!OUT_BF16) { if (accum && j + 1 < FM) fetch_old(j + 1, oldv[(j + 1) & 1]); }
                 __builtin_amdgcn_wave_barrier();           // same-wave LDS accesses complete in order
                 u32x4 wv[PASSES];
                 get_group(j, wv);
-                if constexpr (NSTRIP == 2) { if (j + 1 < FM) put_group(j + 1); }
+                if constexpr (NSTRIP == 2) { if (j + 1 < FM) put_group(j + 1, red_tag); }
                 store_group(j, wv);
                 if constexpr (NSTRIP == 1) {
                     __builtin_amdgcn_wave_barrier();       // reads of the strip precede the next round of writes
-                    if (j + 1 < FM) put_group(j + 1);
+                    if (j + 1 < FM) put_group(j + 1, red_tag);
                 }
             }
+        };
+        if (active) {
+            if constexpr (GROUPED) write_out(std::false_type{});
+            else if (reduce) write_out(std::true_type{});
+            else write_out(std::false_type{});
         }
         if (!more) break;
         cur = nxt;
@@ -596,58 +789,155 @@ static int num_cus_x8() {
     return cached[dev];
 }
 
+__global__ void clear_counters_kernel(int* cnt) { cnt[threadIdx.x] = 0; }
+
+// K-steps per workgroup when `tail` tiles of `kb` K-steps each are shared among `nslots`
+// workgroups as contiguous runs (workgroup s takes steps [s*q, (s+1)*q) of the tiles laid end
+// to end): the smallest q not below an equal share with which no tile is cut into more than
+// two pieces; 0 if only whole tiles qualify (then nothing is shared).
+int tail_share_steps(int tail, int kb, int nslots) {
+    if (tail <= 0 || kb <= 1 || nslots <= tail) return 0;
+    const int64_t total = (int64_t)tail * kb;
+    for (int q = (int)((total + nslots - 1) / nslots); q < kb; ++q) {
+        bool ok = true;
+        for (int t = 0; t < tail && ok; ++t) {
+            const int64_t first = (int64_t)t * kb / q, last = ((int64_t)(t + 1) * kb - 1) / q;
+            ok = last - first <= 1;
+        }
+        if (ok) return q;
+    }
+    return 0;
+}
+
+// Bytes of workspace with which a dense launch of configuration C shares its tail tiles
+// along K (0: the tile count leaves no tail worth sharing).  Mirrors the kernel's rule.
+template <class C>
+static size_t share_bytes(int64_t ntiles, int64_t slots, int kb, int* q_main, int* q_last) {
+    const int64_t nslots = slots / 8, per_xcd = (ntiles + 7) / 8;
+    bool any = false;
+    *q_main = *q_last = 0;
+    for (int x = 0; x < 8; ++x) {
+        int64_t cnt = ntiles - x * per_xcd;
+        cnt = cnt < 0 ? 0 : (cnt > per_xcd ? per_xcd : cnt);
+        const int64_t tail = cnt % nslots;
+        if (!tail_worth_sharing((int)(cnt / nslots), (int)tail, (int)nslots)) continue;
+        const int q = tail_share_steps((int)tail, kb, (int)nslots);
+        if (cnt == per_xcd) *q_main = q; else *q_last = q;
+        any = any || q > 0;
+    }
+    return any ? kCounterBytes + (size_t)slots * 2 * C::BN * C::BM * sizeof(float) : 0;
+}
+
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
-static ds3_status launch_one(GemmParams p, hipStream_t st) {
+static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws_need, hipStream_t st) {
     if (GROUPED) p.tiles_m = (p.M + C::BM - 1) / C::BM + p.G;
     else p.tiles_m = (p.M + C::BM - 1) / C::BM;
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
     const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
+    int q_main = 0, q_last = 0;
+    const size_t need = GROUPED || ntiles <= 0 ? 0 : share_bytes<C>(ntiles, slots, p.K / 128, &q_main, &q_last);
+    if (ws_need) { *ws_need = need; return DS3_OK; }    // size query only
     if (ntiles <= 0) return DS3_OK;
     if (ntiles > (1 << 28)) return DS3_ERR_UNSUPPORTED;
     // 32-bit byte offsets inside one tile's rows, all below the out-of-range marker
     if ((int64_t)(C::BN + 1) * p.ldb + p.K >= (1ll << 31) || (int64_t)(C::BM + 1) * p.lda + p.K >= (1ll << 31))
         return DS3_ERR_UNSUPPORTED;
+    const bool share = ws != nullptr && need > 0;
+    if (share && ws_bytes < need) return DS3_ERR_WORKSPACE;
     // Persistent launch: as many workgroups as fit the chip at once (fewer if there
-    // are fewer tiles), a multiple of 8 so that every XCD gets the same number.
+    // are fewer tiles and no tile is shared along K), a multiple of 8 so that every
+    // XCD gets the same number.
     const int64_t want = ((ntiles + 7) / 8) * 8;
-    const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
-    const unsigned grid = (unsigned)(want < slots ? want : slots);
+    const unsigned grid = (unsigned)(share || want > slots ? slots : want);
+    (void)hipGetLastError();                            // a stale error of earlier, unrelated work is not this launch's
+    if (share) {
+        p.ws_cnt = static_cast<int*>(ws);
+        p.ws_part = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
+        p.share_steps = q_main;
+        p.share_steps_last = q_last;
+        const int kb = p.K / 128;
+        p.share_skew = (2 * q_main == kb && (q_last == 0 || q_last == q_main) && q_main > kShareSkew + 2) ? kShareSkew : 0;
+    }
     gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED, POW2><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
 
 template <class C, bool POW2>
-static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, hipStream_t st) {
+static ds3_status launch_cfg(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, void* ws, size_t wsb, size_t* need, hipStream_t st) {
     const bool bf16 = ct == DS3_BF16;
     if (p.G > 0)
-        return bf16 ? launch_one<C, false, true, true, POW2>(p, st) : launch_one<C, false, false, true, POW2>(p, st);
+        return bf16 ? launch_one<C, false, true, true, POW2>(p, ws, wsb, need, st) : launch_one<C, false, false, true, POW2>(p, ws, wsb, need, st);
     if (mode == DS3_BSCALE_PER_ROW)
-        return bf16 ? launch_one<C, true, true, false, POW2>(p, st) : launch_one<C, true, false, false, POW2>(p, st);
-    return bf16 ? launch_one<C, false, true, false, POW2>(p, st) : launch_one<C, false, false, false, POW2>(p, st);
+        return bf16 ? launch_one<C, true, true, false, POW2>(p, ws, wsb, need, st) : launch_one<C, true, false, false, POW2>(p, ws, wsb, need, st);
+    return bf16 ? launch_one<C, false, true, false, POW2>(p, ws, wsb, need, st) : launch_one<C, false, false, false, POW2>(p, ws, wsb, need, st);
 }
 
 int gemm_num_variants() { return 3; }
 
 template <bool POW2>
-static ds3_status launch_variant(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, hipStream_t st) {
+static ds3_status launch_variant(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, void* ws, size_t wsb, size_t* need,
+                                 hipStream_t st) {
     switch (variant) {
-        case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>, POW2>(p, ct, mode, st);
-        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 3>, POW2>(p, ct, mode, st);
-        case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>, POW2>(p, ct, mode, st);
+        case 0: return launch_cfg<Cfg<256, 256, 4, 2, 2>, POW2>(p, ct, mode, ws, wsb, need, st);
+        case 1: return launch_cfg<Cfg<256, 128, 4, 2, 3>, POW2>(p, ct, mode, ws, wsb, need, st);
+        case 2: return launch_cfg<Cfg<128, 128, 2, 2, 2>, POW2>(p, ct, mode, ws, wsb, need, st);
         default: return DS3_ERR_UNSUPPORTED;
     }
 }
 
-ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st) {
-    if (variant < 0) {
-        // default choice: the 256x256 tile (also the fastest for the ragged expert groups);
-        // the per-row-scale form (more live registers) takes the narrower M tile; problems with
-        // too few large tiles to fill the chip take 128x128 tiles, two workgroups per CU
-        variant = (mode == DS3_BSCALE_PER_ROW) ? 1 : 0;
-        const int64_t big = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
-        if (p.G == 0 && big * 8 < 5 * (int64_t)num_cus_x8()) variant = 2;
+// The tile configuration a shape runs with when the caller does not name one.
+static int default_variant(const GemmParams& p, ds3_bscale mode) {
+    // the 256x256 tile (also the fastest for the ragged expert groups); the per-row-scale
+    // form (more live registers) takes the narrower M tile; problems with too few large
+    // tiles to fill the chip take 128x128 tiles, two workgroups per CU
+    int variant = (mode == DS3_BSCALE_PER_ROW) ? 1 : 0;
+    const int64_t big = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
+    if (p.G == 0 && big * 8 < 5 * (int64_t)num_cus_x8()) variant = 2;
+    return variant;
+}
+
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, void* ws, size_t ws_bytes,
+                       hipStream_t st) {
+    if (variant < 0) variant = default_variant(p, mode);
+    return pow2 ? launch_variant<true>(p, ct, mode, variant, ws, ws_bytes, nullptr, st)
+                : launch_variant<false>(p, ct, mode, variant, ws, ws_bytes, nullptr, st);
+}
+
+__global__ void zero_fill_kernel(uint8_t* c, int64_t row_bytes, int64_t ld_bytes, int64_t rows) {
+    // 16-byte pieces of the rows' valid part, then the bytes of a row that are left
+    const int64_t chunks = row_bytes / 16;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        uint8_t* row = c + r * ld_bytes;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += (int64_t)gridDim.x * blockDim.x)
+            reinterpret_cast<u32x4*>(row)[i] = u32x4{0u, 0u, 0u, 0u};
+        if (blockIdx.x == 0 && threadIdx.x < row_bytes - chunks * 16) row[chunks * 16 + threadIdx.x] = 0;
     }
-    return pow2 ? launch_variant<true>(p, ct, mode, variant, st) : launch_variant<false>(p, ct, mode, variant, st);
+}
+
+ds3_status launch_zero_fill(void* c, ds3_dtype ct, int64_t M, int64_t N, int64_t ldc, hipStream_t st) {
+    const int64_t es = ct == DS3_BF16 ? 2 : 4;
+    const int64_t chunks = N * es / 16;
+    const unsigned gx = (unsigned)(chunks / 256 + 1 > 64 ? 64 : chunks / 256 + 1), gy = (unsigned)(M > 1024 ? 1024 : M);
+    (void)hipGetLastError();
+    zero_fill_kernel<<<dim3(gx, gy), dim3(256), 0, st>>>(static_cast<uint8_t*>(c), N * es, ldc * es, M);
+    return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
+}
+
+ds3_status launch_workspace_init(void* ws, size_t ws_bytes, hipStream_t st) {
+    if (ws_bytes < kCounterBytes) return DS3_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    // a small kernel, not a memset: callers may capture this call into a graph
+    clear_counters_kernel<<<dim3(1), dim3(8 * kTailCounters), 0, st>>>(static_cast<int*>(ws));
+    return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
+}
+
+size_t gemm_workspace_bytes(const GemmParams& p, ds3_bscale mode, int variant) {
+    if (variant < 0) variant = default_variant(p, mode);
+    size_t need = 0;
+    // the requirement depends on the tile configuration only, not on the output type or the scale kind
+    if (launch_variant<false>(p, DS3_BF16, mode, variant, nullptr, 0, &need, nullptr) != DS3_OK) return 0;
+    return need;
 }
 
 }  // namespace ds3

@@ -54,10 +54,24 @@ struct GemmParams {
     int G;
     int tiles_m, tiles_n;  // grouped: tiles_m is the upper bound ceil(M/BM) + G
     int accumulate;
+    int* ws_cnt;           // arrival counters of the tiles shared along K (nullptr: no sharing)
+    float* ws_part;        // partial tiles, two per workgroup
+    int share_steps, share_steps_last;   // K-steps per workgroup in a shared tail (XCDs with a full chunk / the last one)
+    int share_skew;        // K-steps moved from the odd workgroups' runs to the even ones'
 };
 
 // variant: which tile configuration to run (see ds3_gemm.hip); -1 = choose by shape.
 // pow2: every scale is a power of two (the matrix instruction applies them).
-ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st);
+// ws / ws_bytes: device workspace for sharing tail tiles along K (nullptr: never share).
+ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, void* ws, size_t ws_bytes,
+                       hipStream_t st);
+// Bytes of workspace with which launch_gemm shares tail tiles for this shape (0: it would not).
+size_t gemm_workspace_bytes(const GemmParams& p, ds3_bscale mode, int variant);
+// K-steps per workgroup for a shared tail (see ds3_gemm.hip); host logic, exported for its test.
+int tail_share_steps(int tail, int kb, int nslots);
+// Sets the arrival counters at the head of a GEMM workspace to zero.
+ds3_status launch_workspace_init(void* ws, size_t ws_bytes, hipStream_t st);
+// C[M][N] = 0 (the product over an empty inner dimension).
+ds3_status launch_zero_fill(void* c, ds3_dtype ct, int64_t M, int64_t N, int64_t ldc, hipStream_t st);
 
 }  // namespace ds3

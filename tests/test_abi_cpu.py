@@ -31,8 +31,8 @@ def test_every_declared_symbol_is_exported(pkg):
 
 
 def test_status_strings(pkg):
-    seen = {pkg.status_string(i) for i in range(7)}
-    assert len(seen) == 7 and pkg.status_string(0) == "ok" and pkg.status_string(99) == "unknown status"
+    seen = {pkg.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and pkg.status_string(0) == "ok" and pkg.status_string(99) == "unknown status"
 
 
 def test_quantizers_reject_bad_arguments_on_the_host(pkg):
@@ -81,7 +81,59 @@ def test_gemm_rejects_bad_arguments_on_the_host(pkg):
     assert L.ds3_gemm_fp8_bs_v(99, 16, 16, 128, p, 128, p, 1, 16, p, 128, p, 1, 1, 0, p, 1, 16, 0, None, 0, None) == 5
     assert L.ds3_swiglu(p, 4, 12, 24, p, 16, None) == 3
     assert L.ds3_swiglu(None, 4, 16, 32, p, 16, None) == 1
+
+
+def test_gemm_workspace_contract_on_the_host(pkg):
+    """The size query answers without a GPU (it assumes 256 compute units then), a workspace
+    that is too small or misaligned is refused before any launch, and none at all is accepted."""
+    L = pkg._L()
+    buf = (ctypes.c_uint8 * 4096)()
+    p = (ctypes.addressof(buf) + 15) & ~15
+    counters = 8 * 64 * 4
+    # 8192 x 576 on 256 x 256 tiles: 32 x 3 = 96 tiles for 256 workgroups, 12 per XCD: shared (two pieces each)
+    need = pkg.ds3_gemm_workspace_bytes_v(0, 8192, 576, 7168)
+    assert need == counters + 256 * 2 * 256 * 256 * 4
+    # 4096 x 18432: 1152 tiles, half a round is left over: the half-tile split serves it, no workspace
     assert pkg.ds3_gemm_workspace_bytes(4096, 18432, 7168) == 0
+    # 8192 x 24576: 32 x 96 = 3072 tiles, 12 full rounds: nothing to share
+    assert pkg.ds3_gemm_workspace_bytes_v(0, 8192, 24576, 1536) == 0
+    # 2048 x 9216: 288 tiles: a full round and 4 tiles per XCD, an eighth of a round: shared
+    assert pkg.ds3_gemm_workspace_bytes_v(0, 2048, 9216, 512) == need
+    # 256 x 128 tiles (the weight-gradient form's default): 1024 x 640 -> 5 x 4 = 20 tiles, shared
+    assert pkg.ds3_gemm_workspace_bytes_v(-1, 640, 1024, 768, pkg.DS3_BSCALE_PER_ROW) == counters + 256 * 2 * 256 * 128 * 4
+    assert pkg.ds3_gemm_workspace_bytes(0, 16, 128) == 0 and pkg.ds3_gemm_workspace_bytes(16, 16, 100) == 0
+    assert pkg.ds3_gemm_workspace_bytes_v(9, 8192, 576, 7168) == 0
+
+    def call(ws, nbytes, M=8192, N=576, K=7168):
+        return L.ds3_gemm_fp8_bs_v(0, M, N, K, p, K, p, 1, M, p, K, p, K // 128, 1, 0, p, 1, N, 0, ws, nbytes, None)
+
+    assert call(p, need - 1) == 7                 # DS3_ERR_WORKSPACE
+    assert call(p, 0) == 7
+    assert call(p + 4, need) == 3                 # misaligned workspace
+    assert pkg.status_string(7).startswith("workspace")
+
+
+def test_tail_share_steps_never_cuts_a_tile_in_three(pkg):
+    """Brute force over the small cases: the chosen run length q covers the tail with at most
+    `workgroups` runs, is minimal with that property, and no tile meets more than two runs."""
+    f = pkg._L().ds3_gemm_tail_share_steps
+
+    def pieces(tail, kb, q):
+        return max(((t + 1) * kb - 1) // q - (t * kb) // q + 1 for t in range(tail))
+
+    for wgs in (8, 32, 64):
+        for tail in range(1, wgs):
+            for kb in (1, 2, 3, 4, 7, 12, 16, 32, 56, 57, 144):
+                q = f(tail, kb, wgs)
+                q0 = -(-tail * kb // wgs)
+                if q == 0:                       # nothing below a whole tile qualifies
+                    assert all(pieces(tail, kb, c) > 2 for c in range(q0, kb)), (tail, kb, wgs)
+                    continue
+                assert q0 <= q < kb and -(-tail * kb // q) <= wgs, (tail, kb, wgs, q)
+                assert pieces(tail, kb, q) <= 2, (tail, kb, wgs, q)
+                assert all(pieces(tail, kb, c) > 2 for c in range(q0, q)), (tail, kb, wgs, q)
+    assert f(16, 56, 32) == 28 and f(24, 144, 32) == 108 and f(12, 56, 32) == 28
+    assert f(0, 56, 32) == 0 and f(40, 56, 32) == 0
 
 
 def test_later_entry_points_reject_bad_arguments_on_the_host(pkg):

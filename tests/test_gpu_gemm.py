@@ -160,8 +160,9 @@ def test_grouped_small_with_empty_and_ragged_groups(ds3):
             lo, hi = int(off[gi]), int(off[gi + 1])
             if hi == lo:
                 continue
+            # (without a workspace: sharing tiles along K reorders the FP32 additions)
             d = host(ds3.ds3_gemm_fp8_bs(dev(a[lo:hi]), dev(sa[lo:hi]), dev(b[gi]), dev(sb[gi]),
-                                         out_dtype=torch.float32, variant=v))
+                                         out_dtype=torch.float32, variant=v, workspace=None))
             assert np.array_equal(d, c[lo:hi]), (v, gi)
 
 

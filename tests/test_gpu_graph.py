@@ -23,13 +23,18 @@ def test_quantize_and_gemm_in_a_captured_graph(ds3):
     qb = torch.empty((N, K), dtype=torch.uint8, device=x.device)
     sb = torch.empty((N // 128, K // 128), dtype=torch.float32, device=x.device)
     y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    # this shape leaves a partial round of tiles, which the GEMM shares along K through the
+    # workspace: the arrival counters are updated by every replay and left ready for the next
+    ws_bytes = ds3.ds3_gemm_workspace_bytes(M, N, K)
+    assert ws_bytes > 0
+    ws = ds3.new_gemm_workspace(ws_bytes, x.device)     # prepared once, outside the graph
 
     def enqueue(stream):
         r = L.ds3_quant_act_1x128(x.data_ptr(), ds3.DS3_BF16, M, K, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1), stream)
         r |= L.ds3_quant_w_128x128(w.data_ptr(), ds3.DS3_BF16, N, K, K, qb.data_ptr(), K, sb.data_ptr(), stream)
         r |= L.ds3_gemm_fp8_bs(M, N, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1), qb.data_ptr(), K,
                                sb.data_ptr(), sb.stride(0), sb.stride(1), ds3.DS3_BSCALE_128x128, y.data_ptr(), ds3.DS3_BF16, N, 0,
-                               None, 0, stream)
+                               ws.data_ptr(), ws_bytes, stream)
         assert r == 0
 
     side = torch.cuda.Stream()
