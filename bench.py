@@ -251,7 +251,7 @@ def main():
         print(json.dumps({"copy_bytes_read": 256 << 20, "copy_bytes_written": 256 << 20, "launches": 3}))
         return
     if args.workload != "cfg2":
-        from paper_2412_19437_amd import bench_extra
+        import bench_extra
         step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant,
                                                                 args.pow2, args.unfused_swiglu, args.wgrad_from_cache,
                                                                 args.dual_weight_quant)
