@@ -65,12 +65,14 @@ __global__ __launch_bounds__(512) void probe_feed_kernel(const uint8_t* src, uns
 }
 
 ds3_status launch_probe_mfma(int iters, float* out, int blocks, hipStream_t st) {
+    (void)hipGetLastError();
     probe_mfma_kernel<<<dim3(blocks), dim3(512), 0, st>>>(out, iters, 12345u);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
 
 ds3_status launch_probe_feed(const void* src, unsigned window, int row_stride, int iters, unsigned* out, int blocks,
                              hipStream_t st) {
+    (void)hipGetLastError();
     probe_feed_kernel<<<dim3(blocks), dim3(512), 0, st>>>((const uint8_t*)src, window, row_stride, iters, out);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
