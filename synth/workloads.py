@@ -73,38 +73,66 @@ def cfg2_w(n=DENSE_INTER, k=HIDDEN):
 
 
 # ---- config 3: one GPU's share of the MoE experts ---------------------------
-def cfg3_routing(tokens=8192, n_experts=N_ROUTED, top_k=TOP_K, local=LOCAL_EXPERTS, sigma_b=0.02):
+def cfg3_routing(tokens=8192, n_experts=N_ROUTED, top_k=TOP_K, local=LOCAL_EXPERTS, sigma_b=0.02, experts=None):
     """Top-k routing on sigmoid affinities plus a per-expert bias (Section 2.1.2,
     auxiliary-loss-free balancing: the bias enters the top-k selection only).
     Returns (group_sizes[local], group_offsets[local+1], token_ids) where
-    token_ids lists, expert by expert, the tokens routed to experts 0..local-1.
-    Ties go to the lower expert index (stable sort)."""
+    token_ids lists, expert by expert, the tokens routed to experts 0..local-1
+    (or to the experts listed in `experts`).  Ties go to the lower expert index
+    (stable sort)."""
     rng = np.random.default_rng(seed_for(3, 0))
     logits = rng.standard_normal((tokens, n_experts))
     bias = rng.standard_normal(n_experts) * sigma_b
     score = 1.0 / (1.0 + np.exp(-logits)) + bias
     order = np.argsort(-score, axis=1, kind="stable")[:, :top_k]
-    sizes = np.zeros(local, dtype=np.int64)
+    held = list(range(local)) if experts is None else [int(e) for e in experts]
+    sizes = np.zeros(len(held), dtype=np.int64)
     ids = []
-    for e in range(local):
+    for i, e in enumerate(held):
         tok = np.nonzero((order == e).any(axis=1))[0]
-        sizes[e] = tok.size
+        sizes[i] = tok.size
         ids.append(tok)
     offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
     return sizes, offsets, np.concatenate(ids) if ids else np.zeros(0, np.int64)
+
+
+def cfg3_stress_experts(local=LOCAL_EXPERTS, sigma_b=0.05):
+    """The stress variant of config 3: with a wider bias distribution the per-expert load runs from
+    0 to about 4x the mean; the GPU is given the local/2 least and the local/2 most loaded experts
+    (in index order), so that empty and very large groups meet in one call."""
+    sizes, _, _ = cfg3_routing(local=N_ROUTED, sigma_b=sigma_b)
+    order = np.argsort(sizes, kind="stable")
+    return sorted(int(e) for e in np.concatenate([order[:local // 2], order[-(local // 2):]]))
 
 
 def cfg3_tokens(total_rows, k=HIDDEN):
     return normal((total_rows, k), 1.0, seed_for(3, 1))
 
 
+def _expert_weight(tensor, e, shape):
+    """One expert's weight ~N(0, 0.02), BF16-representable; every expert has a random stream of its
+    own (seed sequence [seed_for(3, tensor), e]), so any subset can be drawn without the others."""
+    rng = np.random.default_rng([seed_for(3, tensor), int(e)])
+    return bf16_round(rng.standard_normal(shape, dtype=np.float32) * np.float32(0.02))
+
+
+def cfg3_w13_expert(e, inter=MOE_INTER, k=HIDDEN):
+    """Fused gate|up weight of expert e: [2*inter][k]; rows 0..inter-1 gate, rest up."""
+    return _expert_weight(2, e, (2 * inter, k))
+
+
+def cfg3_w2_expert(e, inter=MOE_INTER, k=HIDDEN):
+    """Down-projection weight of expert e: [k][inter]."""
+    return _expert_weight(3, e, (k, inter))
+
+
 def cfg3_w13(g=LOCAL_EXPERTS, inter=MOE_INTER, k=HIDDEN):
-    """Fused gate|up weight per expert: [g][2*inter][k]; rows 0..inter-1 gate, rest up."""
-    return normal((g, 2 * inter, k), 0.02, seed_for(3, 2))
+    """Fused gate|up weights of experts 0..g-1: [g][2*inter][k]."""
+    return np.stack([cfg3_w13_expert(e, inter, k) for e in range(g)])
 
 
 def cfg3_w2(g=LOCAL_EXPERTS, inter=MOE_INTER, k=HIDDEN):
-    return normal((g, k, inter), 0.02, seed_for(3, 3))
+    return np.stack([cfg3_w2_expert(e, inter, k) for e in range(g)])
 
 
 # ---- config 4: backward of the config-2 layer -------------------------------

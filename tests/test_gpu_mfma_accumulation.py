@@ -1,0 +1,76 @@
+"""What the matrix instruction's own sum of 128 FP8 products is worth (the report raises the
+same question for its hardware in Section 3.3.2, "Increasing Accumulation Precision": it
+measures about 14 bits there and answers by promoting every 128 elements to FP32 -- this path
+promotes every single instruction).  The FP32-output tolerance of the GEMM tests rests on
+this characterisation.
+
+One K = 128 block, unit scales, random codes over the whole E4M3 range, FP32 output: every
+product is exact in FP32 (two 4-bit significands), so what differs from the exact sum is the
+instruction's internal alignment / rounding alone.  The error is bounded relative to the sum
+of the magnitudes S = sum_k |a_k b_k| (a bound relative to the result itself cannot exist
+under cancellation), and it does not grow with K: more blocks are added in FP32 by the
+vector ALU, one rounding of 2^-24 per block.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ds3_oracle as orc
+from tests._gpu_util import announce, dev, host, normwise
+
+pytestmark = pytest.mark.gpu
+
+# Bounds, each about twice what MI355X measures (the test prints the measured values):
+#   element-wise  |C - exact| <= BETA * sum_k |a_k b_k|        measured 1.6e-4 (2^-12.6) at K = 128
+#   its root mean square over the outputs                       measured 2.4e-5
+#   normwise      ||C - exact|| / ||exact||                     measured 5.1e-5  -> TOL_F32 = 1e-4 in the GEMM tests
+# The matrix unit keeps about 13 bits below the sum of the magnitudes -- the same order as the
+# "around 14 bits" the report quotes for its hardware; here it applies to ONE 128-element
+# interval, never to a longer sum.
+BETA = 2.0 ** -11.6
+RMS = 5e-5
+TOL_F32 = 1e-4
+
+
+def _rand_codes(rng, shape):
+    c = rng.integers(0, 0x7F, size=shape).astype(np.uint8)          # all finite magnitudes, 2^-9 .. 448
+    return c | (rng.integers(0, 2, size=shape) << 7).astype(np.uint8)
+
+
+def test_block_sum_error_is_bounded_by_the_magnitude_sum_and_does_not_grow_with_k(ds3):
+    rng = np.random.default_rng(71)
+    m, n = 256, 256
+    seen = {}
+    for k in (128, 1024, 8192):
+        announce(f"MFMA accumulation K={k}")
+        a, b = _rand_codes(rng, (m, k)), _rand_codes(rng, (n, k))
+        one_a = np.ones((m, k // 128), np.float32)
+        one_b = np.ones((n // 128, k // 128), np.float32)
+        ref = orc.gemm_fp8_bs(a, one_a, b, one_b)                   # exact in FP64: products of two 4-bit significands
+        mag = np.abs(orc.e4m3_decode(a)) @ np.abs(orc.e4m3_decode(b)).T
+        for v in range(ds3.ds3_gemm_num_variants()):
+            c = host(ds3.ds3_gemm_fp8_bs(dev(a), dev(one_a), dev(b), dev(one_b), out_dtype=torch.float32, variant=v,
+                                         workspace=None)).astype(np.float64)
+            rel = np.abs(c - ref) / mag
+            rms, nw = float(np.sqrt(np.mean(rel ** 2))), normwise(c, ref)
+            print(f"K={k} variant {v}: max |err| / sum|ab| = {rel.max():.3e} (2^{np.log2(rel.max()):.1f}), rms {rms:.3e}, "
+                  f"normwise {nw:.3e}, ||sum|ab||| / ||C|| = {np.linalg.norm(mag) / np.linalg.norm(ref):.2f}")
+            assert rel.max() <= BETA and rms <= RMS and nw <= TOL_F32, (k, v)
+            seen[(k, v)] = (float(rel.max()), rms, nw)
+    # longer sums are no worse: the blocks' errors are independent and the FP32 additions
+    # between them are exact to 2^-24
+    for v in range(ds3.ds3_gemm_num_variants()):
+        for k in (1024, 8192):
+            assert seen[(k, v)][1] <= 1.25 * seen[(128, v)][1] and seen[(k, v)][2] <= 1.25 * seen[(128, v)][2], (k, v, seen)
+
+
+def test_small_integers_are_summed_exactly(ds3):
+    """Products that are small integers align without loss: the block sum is exact."""
+    announce("MFMA accumulation exact integers")
+    rng = np.random.default_rng(72)
+    table = np.array([0x00, 0x38, 0x40, 0x44, 0x48, 0xB8, 0xC0, 0xC4, 0xC8], dtype=np.uint8)   # 0, +-1, +-2, +-3, +-4
+    a, b = table[rng.integers(0, 9, (64, 128))], table[rng.integers(0, 9, (64, 128))]
+    one = np.ones((64, 1), np.float32)
+    ref = orc.gemm_fp8_bs(a, one, b, np.ones((1, 1), np.float32))
+    c = host(ds3.ds3_gemm_fp8_bs(dev(a), dev(one), dev(b), dev(np.ones((1, 1), np.float32)), out_dtype=torch.float32))
+    assert np.array_equal(c.astype(np.float64), ref)
