@@ -598,23 +598,21 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         [[maybe_unused]] __amdgpu_buffer_rsrc_t rs_other = cur.rs_a;
         [[maybe_unused]] const int toff = tid * 16;
         if constexpr (!GROUPED) {
-            const int q = share_q;
             if (pieces > 1) {
                 constexpr int TILE_F = BN * BM;            // floats of one partial tile
                 int* const cnt = p.ws_cnt + xcd * kTailCounters + tail_tile;
                 // A partial tile is stored lane by lane: accumulator (i, j) of thread t at float
                 // ((i * FM + j) * NT + t) * 4.  Buffer addressing keeps the per-thread part of
                 // every address in one register (the accumulators leave few to spare).
-                auto part_rsrc = [&](int wg_slot, int which) {
-                    float* base = p.ws_part + (int64_t)((wg_slot * 8 + xcd) * 2 + which) * TILE_F;
+                // two partial tiles per shared tile, one per piece (both pieces may store when they
+                // finish together): [XCD][tail tile][piece]
+                auto part_of = [&](int k) {                // partial tile of the tile's k-th piece, k = 0, 1 in K order
+                    float* base = p.ws_part + (int64_t)((xcd * p.share_tail_max + tail_tile) * 2 + k) * TILE_F;
                     return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, TILE_F * 4, 0x00020000);
                 };
-                auto part_of = [&](int k) {                // partial tile of the tile's k-th piece
-                    const int s2 = first_slot + k;
-                    return part_rsrc(s2, (min(s2 * q, tail_steps) / KB == tail_tile) ? 0 : 1);
-                };
+                const int me = slot - first_slot;          // 0: this workgroup holds the tile's first piece, 1: its second
                 auto store_mine = [&]() {
-                    const __amdgpu_buffer_rsrc_t rs = part_rsrc(slot, my_part);
+                    const __amdgpu_buffer_rsrc_t rs = part_of(me);
 #pragma unroll
                     for (int i = 0; i < FN; ++i)
 #pragma unroll
@@ -642,7 +640,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                     continue;
                 }
                 reduce = true;                             // the epilogue adds the other piece in on its way out
-                rs_other = part_of(1 - (slot - first_slot));
+                rs_other = part_of(1 - me);
             }
         }
 
@@ -812,10 +810,9 @@ int tail_share_steps(int tail, int kb, int nslots) {
 // Bytes of workspace with which a dense launch of configuration C shares its tail tiles
 // along K (0: the tile count leaves no tail worth sharing).  Mirrors the kernel's rule.
 template <class C>
-static size_t share_bytes(int64_t ntiles, int64_t slots, int kb, int* q_main, int* q_last) {
+static size_t share_bytes(int64_t ntiles, int64_t slots, int kb, int* q_main, int* q_last, int* tail_max) {
     const int64_t nslots = slots / 8, per_xcd = (ntiles + 7) / 8;
-    bool any = false;
-    *q_main = *q_last = 0;
+    *q_main = *q_last = *tail_max = 0;
     for (int x = 0; x < 8; ++x) {
         int64_t cnt = ntiles - x * per_xcd;
         cnt = cnt < 0 ? 0 : (cnt > per_xcd ? per_xcd : cnt);
@@ -823,9 +820,10 @@ static size_t share_bytes(int64_t ntiles, int64_t slots, int kb, int* q_main, in
         if (!tail_worth_sharing((int)(cnt / nslots), (int)tail, (int)nslots)) continue;
         const int q = tail_share_steps((int)tail, kb, (int)nslots);
         if (cnt == per_xcd) *q_main = q; else *q_last = q;
-        any = any || q > 0;
+        if (q > 0 && tail > *tail_max) *tail_max = (int)tail;
     }
-    return any ? kCounterBytes + (size_t)slots * 2 * C::BN * C::BM * sizeof(float) : 0;
+    // arrival counters, then two partial tiles for every tile that may be shared
+    return *tail_max ? kCounterBytes + (size_t)8 * *tail_max * 2 * C::BN * C::BM * sizeof(float) : 0;
 }
 
 template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
@@ -835,8 +833,8 @@ static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws
     p.tiles_n = (p.N + C::BN - 1) / C::BN;
     const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
     const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
-    int q_main = 0, q_last = 0;
-    const size_t need = GROUPED || ntiles <= 0 ? 0 : share_bytes<C>(ntiles, slots, p.K / 128, &q_main, &q_last);
+    int q_main = 0, q_last = 0, tail_max = 0;
+    const size_t need = GROUPED || ntiles <= 0 ? 0 : share_bytes<C>(ntiles, slots, p.K / 128, &q_main, &q_last, &tail_max);
     if (ws_need) { *ws_need = need; return DS3_OK; }    // size query only
     if (ntiles <= 0) return DS3_OK;
     if (ntiles > (1 << 28)) return DS3_ERR_UNSUPPORTED;
@@ -856,6 +854,7 @@ static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws
         p.ws_part = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
         p.share_steps = q_main;
         p.share_steps_last = q_last;
+        p.share_tail_max = tail_max;
         const int kb = p.K / 128;
         p.share_skew = (2 * q_main == kb && (q_last == 0 || q_last == q_main) && q_main > kShareSkew + 2) ? kShareSkew : 0;
     }

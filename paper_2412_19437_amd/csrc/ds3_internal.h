@@ -55,7 +55,8 @@ struct GemmParams {
     int tiles_m, tiles_n;  // grouped: tiles_m is the upper bound ceil(M/BM) + G
     int accumulate;
     int* ws_cnt;           // arrival counters of the tiles shared along K (nullptr: no sharing)
-    float* ws_part;        // partial tiles, two per workgroup
+    float* ws_part;        // partial tiles [XCD][share_tail_max][2]
+    int share_tail_max;    // most shared tiles any XCD has
     int share_steps, share_steps_last;   // K-steps per workgroup in a shared tail (XCDs with a full chunk / the last one)
     int share_skew;        // K-steps moved from the odd workgroups' runs to the even ones'
 };

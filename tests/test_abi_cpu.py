@@ -90,19 +90,25 @@ def test_gemm_workspace_contract_on_the_host(pkg):
     buf = (ctypes.c_uint8 * 4096)()
     p = (ctypes.addressof(buf) + 15) & ~15
     counters = 8 * 64 * 4
+
+    def need(shared_tiles_per_xcd, tile_floats):   # arrival counters + two FP32 partial tiles per shared tile
+        return counters + 8 * shared_tiles_per_xcd * 2 * tile_floats * 4
+
     # 8192 x 576 on 256 x 256 tiles: 32 x 3 = 96 tiles for 256 workgroups, 12 per XCD: shared (two pieces each)
-    need = pkg.ds3_gemm_workspace_bytes_v(0, 8192, 576, 7168)
-    assert need == counters + 256 * 2 * 256 * 256 * 4
+    assert pkg.ds3_gemm_workspace_bytes_v(0, 8192, 576, 7168) == need(12, 256 * 256)
     # 4096 x 18432: 1152 tiles, half a round is left over: the half-tile split serves it, no workspace
     assert pkg.ds3_gemm_workspace_bytes(4096, 18432, 7168) == 0
     # 8192 x 24576: 32 x 96 = 3072 tiles, 12 full rounds: nothing to share
     assert pkg.ds3_gemm_workspace_bytes_v(0, 8192, 24576, 1536) == 0
     # 2048 x 9216: 288 tiles: a full round and 4 tiles per XCD, an eighth of a round: shared
-    assert pkg.ds3_gemm_workspace_bytes_v(0, 2048, 9216, 512) == need
-    # 256 x 128 tiles (the weight-gradient form's default): 1024 x 640 -> 5 x 4 = 20 tiles, shared
-    assert pkg.ds3_gemm_workspace_bytes_v(-1, 640, 1024, 768, pkg.DS3_BSCALE_PER_ROW) == counters + 256 * 2 * 256 * 128 * 4
+    assert pkg.ds3_gemm_workspace_bytes_v(0, 2048, 9216, 512) == need(4, 256 * 256)
+    # 256 x 128 tiles (the weight-gradient form's large-shape default): 640 x 1024 -> 5 x 4 = 20 tiles, at most 3 per XCD
+    assert pkg.ds3_gemm_workspace_bytes_v(1, 640, 1024, 768, pkg.DS3_BSCALE_PER_ROW) == need(3, 256 * 128)
+    # few tiles: the default choice is 128 x 128 tiles, 5 x 8 = 40 of them, 5 per XCD
+    assert pkg.ds3_gemm_workspace_bytes_v(-1, 640, 1024, 768, pkg.DS3_BSCALE_PER_ROW) == need(5, 128 * 128)
     assert pkg.ds3_gemm_workspace_bytes(0, 16, 128) == 0 and pkg.ds3_gemm_workspace_bytes(16, 16, 100) == 0
     assert pkg.ds3_gemm_workspace_bytes_v(9, 8192, 576, 7168) == 0
+    need = need(12, 256 * 256)
 
     def call(ws, nbytes, M=8192, N=576, K=7168):
         return L.ds3_gemm_fp8_bs_v(0, M, N, K, p, K, p, 1, M, p, K, p, K // 128, 1, 0, p, 1, N, 0, ws, nbytes, None)
