@@ -153,6 +153,26 @@ ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ds3_gemm_fp8_bs for callers that cannot allocate device memory -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc -- and so cannot bring
+ * a workspace: the same operation, arguments and results as ds3_gemm_fp8_bs with a
+ * workspace of ds3_gemm_workspace_bytes() bytes, but the partial sums of shared tiles go
+ * through a statically allocated device array of the library
+ * (ds3_gemm_noalloc_scratch_bytes() = 76 MiB + 2 KiB, held by every GPU the library is
+ * loaded on until the process ends).  The call allocates and frees nothing.  A shape that
+ * would need more than the array holds is refused with DS3_ERR_WORKSPACE (no shape does on
+ * a device of up to 256 compute units).  All calls on one GPU share the array: calls that
+ * may run at the same time on one GPU race; calls on one stream, or ordered by events, are fine.
+ */
+ds3_status ds3_gemm_fp8_bs_noalloc(int64_t M, int64_t N, int64_t K,
+                                   const uint8_t* a, int64_t lda,
+                                   const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                   const uint8_t* b, int64_t ldb,
+                                   const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode,
+                                   void* c, ds3_dtype ct, int64_t ldc, int accumulate, void* stream);
+size_t ds3_gemm_noalloc_scratch_bytes(void);
+
+/*
  * Grouped block-scaled GEMM over MoE experts (Section 2.1.2: each routed
  * expert multiplies only the tokens routed to it; no token is dropped, so
  * groups are ragged and may be empty).  For expert g, rows

@@ -24,7 +24,7 @@ DS3_BSCALE_128x128, DS3_BSCALE_PER_ROW = 0, 1
 SYMBOLS = [
     "ds3_quant_act_1x128", "ds3_quant_act_128x1", "ds3_quant_w_128x128",
     "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_gemm_fp8_bs_v", "ds3_grouped_gemm_fp8_bs_v",
-    "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_gemm_workspace_bytes_v", "ds3_gemm_tail_share_steps", "ds3_gemm_workspace_init", "ds3_swiglu", "ds3_status_string",
+    "ds3_gemm_num_variants", "ds3_gemm_workspace_bytes", "ds3_gemm_workspace_bytes_v", "ds3_gemm_tail_share_steps", "ds3_gemm_workspace_init", "ds3_gemm_fp8_bs_noalloc", "ds3_gemm_noalloc_scratch_bytes", "ds3_swiglu", "ds3_status_string",
     "ds3_quant_act_1x128_pow2", "ds3_quant_act_128x1_pow2", "ds3_quant_w_128x128_pow2",
     "ds3_gemm_fp8_bs_pow2", "ds3_grouped_gemm_fp8_bs_pow2",
     "ds3_probe_mfma_fp8", "ds3_probe_lds_feed", "ds3_swiglu_quant_1x128", "ds3_swiglu_quant_1x128_pow2",
@@ -56,6 +56,9 @@ def _load() -> ctypes.CDLL:
     lib.ds3_gemm_fp8_bs.argtypes = gemm
     lib.ds3_gemm_fp8_bs_v.argtypes = [i32] + gemm
     lib.ds3_gemm_fp8_bs_pow2.argtypes = [i32] + gemm
+    lib.ds3_gemm_fp8_bs_noalloc.argtypes = gemm[:-3] + [vp]
+    lib.ds3_gemm_noalloc_scratch_bytes.argtypes = []
+    lib.ds3_gemm_noalloc_scratch_bytes.restype = sz
     grouped = [i32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i32, i64, vp, sz, vp]
     lib.ds3_grouped_gemm_fp8_bs.argtypes = grouped
     lib.ds3_grouped_gemm_fp8_bs_v.argtypes = [i32] + grouped
@@ -440,6 +443,20 @@ def ds3_retile_1x128_to_128x1_pow2(q: torch.Tensor, s: torch.Tensor, k_major_sca
 
 def ds3_gemm_num_variants() -> int:
     return int(_L().ds3_gemm_num_variants())
+
+
+def ds3_gemm_fp8_bs_noalloc(a, sa, b, sb, c: torch.Tensor, sb_mode: int = DS3_BSCALE_128x128, accumulate: bool = False):
+    """ds3_gemm_fp8_bs into the caller's `c` through the entry point that allocates nothing."""
+    m, k, lda = _rows2d(a, "a")
+    n, kb_, ldb = _rows2d(b, "b")
+    if kb_ != k or tuple(c.shape) != (m, n):
+        raise ValueError("shapes disagree")
+    _, _, ldc = _rows2d(c, "c")
+    st = _L().ds3_gemm_fp8_bs_noalloc(m, n, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), ldb,
+                                      sb.data_ptr(), sb.stride(0), sb.stride(1), sb_mode, c.data_ptr(), _dt(c), ldc,
+                                      int(accumulate), _stream())
+    _check(st, "ds3_gemm_fp8_bs_noalloc")
+    return c
 
 
 def ds3_gemm_workspace_bytes(m: int, n: int, k: int) -> int:

@@ -13,6 +13,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int64_t esize(ds3_dtype t) { return t == DS3_BF16 ? 2 : 4; }
 inline bool dtype_ok(ds3_dtype t) { return t == DS3_BF16 || t == DS3_F32; }
 constexpr int64_t kMaxDim = (1ll << 31) - 1;
+// internal marker: "use the library's own statically allocated workspace" (16-byte aligned, never a device address)
+void* const kStaticScratch = reinterpret_cast<void*>(static_cast<uintptr_t>(16));
 
 ds3_status check_quant(const void* x, ds3_dtype xt, int64_t rows, int64_t cols, int64_t ldx, const void* q,
                        int64_t ldq_min, int64_t ldq, const void* s) {
@@ -71,6 +73,7 @@ ds3_status gemm_common(bool pow2, int variant, int32_t G, const int32_t* offs, i
     p.b_group_stride = N * ldb;
     p.sb_group_stride = ((N + 127) / 128) * (K / 128);
     p.accumulate = accumulate;
+    if (workspace == kStaticScratch) return launch_gemm_static_scratch(p, ct, mode, variant, pow2, static_cast<hipStream_t>(stream));
     return launch_gemm(p, ct, mode, variant, pow2, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
@@ -168,6 +171,16 @@ ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K, const uint8_t* a, in
     return ds3_gemm_fp8_bs_v(-1, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb, sb_stride_row,
                              sb_stride_kb, sb_mode, c, ct, ldc, accumulate, workspace, workspace_bytes, stream);
 }
+
+ds3_status ds3_gemm_fp8_bs_noalloc(int64_t M, int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                                   int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
+                                   const float* sb, int64_t sb_stride_row, int64_t sb_stride_kb, ds3_bscale sb_mode, void* c,
+                                   ds3_dtype ct, int64_t ldc, int accumulate, void* stream) {
+    return gemm_common(false, -1, 0, nullptr, M, N, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb, sb, sb_stride_row,
+                       sb_stride_kb, sb_mode, c, ct, ldc, accumulate, kStaticScratch, 0, stream);
+}
+
+size_t ds3_gemm_noalloc_scratch_bytes(void) { return gemm_static_scratch_bytes(); }
 
 ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* group_offsets, int64_t total_rows,
                                      int64_t N, int64_t K, const uint8_t* a, int64_t lda, const float* sa,

@@ -26,6 +26,7 @@
 // issued into the freed stage and the first fragments and scales of K-step
 // kb+1 are read from LDS, so the matrix pipe never waits for LDS at the start
 // of a K-step.
+#include <mutex>
 #include <type_traits>
 
 #include "ds3_dev.h"
@@ -922,6 +923,44 @@ ds3_status launch_zero_fill(void* c, ds3_dtype ct, int64_t M, int64_t N, int64_t
     zero_fill_kernel<<<dim3(gx, gy), dim3(256), 0, st>>>(static_cast<uint8_t*>(c), N * es, ldc * es, M);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
+
+// ---- a workspace of the library's own, for callers that cannot allocate -----------------
+// Large enough for every shape on a 256-CU device: at most 19 of an XCD's 32 workgroups' tiles
+// are shared (the rule above), two partial tiles of 256 x 256 floats each, eight XCDs.  Each
+// device the library runs on holds its own copy from the moment the code object is loaded
+// (zero-filled then, which is what the arrival counters need; every call leaves them so).
+constexpr size_t kScratchBytes = kCounterBytes + (size_t)8 * 19 * 2 * 256 * 256 * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// The array's device address, per device (its name is only a host-side handle).
+static ds3_status scratch_address(void** out, hipStream_t st) {
+    static std::mutex mu;
+    static void* addr[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DS3_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return DS3_ERR_LAUNCH;
+        // the counters start even whatever ran before: once per device, in stream order before the first use
+        (void)hipGetLastError();
+        clear_counters_kernel<<<dim3(1), dim3(8 * kTailCounters), 0, st>>>(static_cast<int*>(ptr));
+        if (hipGetLastError() != hipSuccess) return DS3_ERR_LAUNCH;
+        addr[dev] = ptr;
+    }
+    *out = addr[dev];
+    return DS3_OK;
+}
+
+ds3_status launch_gemm_static_scratch(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st) {
+    void* ws = nullptr;
+    const ds3_status rc = scratch_address(&ws, st);
+    if (rc != DS3_OK) return rc;
+    // (a shape that asked for more than the array holds would be refused with DS3_ERR_WORKSPACE)
+    return launch_gemm(p, ct, mode, variant, pow2, ws, kScratchBytes, st);
+}
+
+size_t gemm_static_scratch_bytes() { return kScratchBytes; }
 
 ds3_status launch_workspace_init(void* ws, size_t ws_bytes, hipStream_t st) {
     if (ws_bytes < kCounterBytes) return DS3_ERR_WORKSPACE;

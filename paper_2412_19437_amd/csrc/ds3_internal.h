@@ -66,6 +66,9 @@ struct GemmParams {
 // ws / ws_bytes: device workspace for sharing tail tiles along K (nullptr: never share).
 ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, void* ws, size_t ws_bytes,
                        hipStream_t st);
+// As launch_gemm with the library's own statically allocated workspace (one per device).
+ds3_status launch_gemm_static_scratch(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st);
+size_t gemm_static_scratch_bytes();
 // Bytes of workspace with which launch_gemm shares tail tiles for this shape (0: it would not).
 size_t gemm_workspace_bytes(const GemmParams& p, ds3_bscale mode, int variant);
 // K-steps per workgroup for a shared tail (see ds3_gemm.hip); host logic, exported for its test.

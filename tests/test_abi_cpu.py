@@ -108,6 +108,8 @@ def test_gemm_workspace_contract_on_the_host(pkg):
     assert pkg.ds3_gemm_workspace_bytes_v(-1, 640, 1024, 768, pkg.DS3_BSCALE_PER_ROW) == need(5, 128 * 128)
     assert pkg.ds3_gemm_workspace_bytes(0, 16, 128) == 0 and pkg.ds3_gemm_workspace_bytes(16, 16, 100) == 0
     assert pkg.ds3_gemm_workspace_bytes_v(9, 8192, 576, 7168) == 0
+    # the statically allocated workspace of the entry point that allocates nothing covers the largest need
+    assert pkg._L().ds3_gemm_noalloc_scratch_bytes() == need(19, 256 * 256)
     need = need(12, 256 * 256)
 
     def call(ws, nbytes, M=8192, N=576, K=7168):
