@@ -363,6 +363,45 @@ ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inte
                                        float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
 
 /*
+ * Grouped gate|up projection with SwiGLU and the 1x128 quantization of its
+ * output done on each GEMM tile before it leaves the chip (Section 3.3.2,
+ * Online Quantization, and Section 3.3.3, Low-Precision Activation: the input
+ * of the down projection is the SwiGLU output in FP8; Section 3.5.2 asks for
+ * the cast to be fused with its producer).  Neither the projection's output h
+ * nor the BF16 activation reaches HBM.
+ *   a, sa, group_offsets, total_rows, K   as in ds3_grouped_gemm_fp8_bs
+ *   b   [G][2*inter][ldb] codes of the fused gate|up weight with its rows
+ *       INTERLEAVED in blocks of 128: rows [256 t, 256 t + 128) are gate rows
+ *       [128 t, 128 t + 128), rows [256 t + 128, 256 t + 256) the up rows of
+ *       the same range, so that both halves of an output tile meet in one
+ *       GEMM tile.  Whole 128x128 blocks move, so the codes and scales are
+ *       those of the gate and up matrices quantized on their own.
+ *   sb  [G][2*inter/128][K/128] in the same block-row order
+ *   q   [total_rows][ldq] codes of silu(gate) * up, `inter` valid columns
+ *   s   scales of q, element (row, tile t) at s[row * s_stride_row + t * s_stride_kb]
+ * inter % 128 == 0, K > 0; q 16-byte aligned, ldq % 16 == 0, ldq >= inter.
+ * Result: bit for bit that of ds3_grouped_gemm_fp8_bs (BF16 output, tile
+ * configuration 0) on the same operands followed by ds3_swiglu_quant_1x128
+ * on its de-interleaved output.  The _pow2 form takes operands whose scales
+ * are all powers of two and writes power-of-two scales.
+ * Rows at or beyond group_offsets[G] are left untouched.
+ */
+ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                                int64_t inter, int64_t K,
+                                                const uint8_t* a, int64_t lda,
+                                                const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                                const uint8_t* b, int64_t ldb, const float* sb,
+                                                uint8_t* q, int64_t ldq,
+                                                float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(int32_t G, const int32_t* group_offsets, int64_t total_rows,
+                                                     int64_t inter, int64_t K,
+                                                     const uint8_t* a, int64_t lda,
+                                                     const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
+                                                     const uint8_t* b, int64_t ldb, const float* sb,
+                                                     uint8_t* q, int64_t ldq,
+                                                     float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+
+/*
  * RMSNorm fused with the 1x128 quantization of its output, the input of the
  * Linear that follows the normalisation (Section 3.3: normalisation operators
  * keep their original precision; Section 3.5.2 asks for the FP8 cast to be fused

@@ -32,6 +32,7 @@ SYMBOLS = [
     "ds3_quant_w_128x128_dual", "ds3_quant_w_128x128_dual_pow2",
     "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2", "ds3_adamw_bf16_states",
     "ds3_quant_act_1x128_e5m6", "ds3_dequant_e5m6",
+    "ds3_grouped_gemm_swiglu_quant_fp8_bs", "ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2",
 ]
 
 
@@ -65,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.ds3_grouped_gemm_fp8_bs_pow2.argtypes = [i32] + grouped
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
     lib.ds3_swiglu_quant_1x128.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
+    for name in ("ds3_grouped_gemm_swiglu_quant_fp8_bs", "ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2"):
+        getattr(lib, name).argtypes = [ctypes.c_int32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i64, vp, i64, i64, vp]
     lib.ds3_swiglu_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1_pow2.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
@@ -417,6 +420,36 @@ def ds3_swiglu_quant_1x128(h: torch.Tensor, k_major_scales: bool = True):
 def ds3_swiglu_quant_1x128_pow2(h: torch.Tensor, k_major_scales: bool = True):
     """As ds3_swiglu_quant_1x128 with power-of-two scales."""
     return _swiglu_quant("ds3_swiglu_quant_1x128_pow2", h, k_major_scales)
+
+
+def _grouped_swiglu_quant(entry, a, sa, group_offsets, b, sb, k_major_scales):
+    m, k, lda = _rows2d(a, "a")
+    g, n, kk = b.shape
+    if kk != k or n % 256 or not b.is_contiguous() or not sb.is_contiguous():
+        raise ValueError("b must be contiguous [G][2*inter][K] with inter % 128 == 0, sb contiguous")
+    if group_offsets.dtype != torch.int32 or group_offsets.numel() != g + 1:
+        raise ValueError("group_offsets must be int32 of length G+1")
+    inter = n // 2
+    q = _codes(m, inter, a.device)
+    s = _scales(m, inter // 128, a.device, k_major_scales)
+    st = getattr(_L(), entry)(g, group_offsets.data_ptr(), m, inter, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0),
+                              sa.stride(1), b.data_ptr(), k, sb.data_ptr(), q.data_ptr(), inter, s.data_ptr(),
+                              s.stride(0), s.stride(1), _stream())
+    _check(st, entry)
+    return q, s
+
+
+def ds3_grouped_gemm_swiglu_quant_fp8_bs(a, sa, group_offsets, b, sb, k_major_scales: bool = True):
+    """Grouped gate|up projection with SwiGLU and the 1x128 quantizer in its epilogue.
+    b: [G][2*inter][K] codes with gate and up rows interleaved in blocks of 128
+    (128 gate rows, the 128 up rows of the same range, ...), sb in the same order.
+    Returns (codes [rows][inter], scales) of silu(gate) * up; rows beyond the last group are not written."""
+    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs", a, sa, group_offsets, b, sb, k_major_scales)
+
+
+def ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(a, sa, group_offsets, b, sb, k_major_scales: bool = True):
+    """As ds3_grouped_gemm_swiglu_quant_fp8_bs: power-of-two scales in, power-of-two scales out."""
+    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2", a, sa, group_offsets, b, sb, k_major_scales)
 
 
 def _retile(entry: str, q: torch.Tensor, s: torch.Tensor, k_major_scales: bool):

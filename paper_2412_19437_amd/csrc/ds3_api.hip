@@ -208,6 +208,62 @@ ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int6
                                      b, ldb, sb, c, ct, ldc, workspace, workspace_bytes, stream);
 }
 
+static ds3_status grouped_swiglu_quant(bool pow2, int32_t G, const int32_t* offs, int64_t M, int64_t inter, int64_t K,
+                                       const uint8_t* a, int64_t lda, const float* sa, int64_t sar, int64_t sak,
+                                       const uint8_t* b, int64_t ldb, const float* sb, uint8_t* q, int64_t ldq, float* s,
+                                       int64_t sor, int64_t sok, void* stream) {
+    if (G < 0 || M < 0 || inter < 0 || K < 0) return DS3_ERR_SHAPE;
+    if (K % 128 || inter % 128) return DS3_ERR_SHAPE;
+    if (G == 0 || M == 0 || inter == 0) return DS3_OK;
+    if (!q || !s) return DS3_ERR_NULL;
+    if (ldq < inter) return DS3_ERR_SHAPE;
+    if (!aligned16(q) || ldq % 16 || (reinterpret_cast<uintptr_t>(s) & 3u)) return DS3_ERR_ALIGN;
+    const int64_t N = 2 * inter;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || G > 1023) return DS3_ERR_UNSUPPORTED;
+    if (K == 0) return DS3_ERR_SHAPE;                    // the quantised activation of an empty product is not offered
+    if (!a || !b || !sa || !sb || !offs) return DS3_ERR_NULL;
+    if (lda < K || ldb < K) return DS3_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(b) || lda % 16 || ldb % 16) return DS3_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DS3_ERR_ALIGN;
+    if ((int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
+    {
+        const int64_t kbm = K / 128, lim = (1ll << 29) - 1;
+        if (sar < 0 || sak < 0) return DS3_ERR_UNSUPPORTED;
+        if ((M - 1) > lim / (sar > 0 ? sar : 1) || (kbm - 1) > lim / (sak > 0 ? sak : 1) ||
+            (M - 1) * sar + (kbm - 1) * sak > lim)
+            return DS3_ERR_UNSUPPORTED;
+        if ((int64_t)G * (N / 128) * kbm > lim) return DS3_ERR_UNSUPPORTED;
+    }
+    GemmParams p{};
+    p.a = a; p.b = b; p.sa = sa; p.sb = sb; p.c = nullptr;
+    p.lda = lda; p.ldb = ldb; p.ldc = 0;
+    p.sar = sar; p.sak = sak; p.sbr = K / 128; p.sbk = 1;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K; p.G = G;
+    p.group_offsets = offs;
+    p.b_group_stride = N * ldb;
+    p.sb_group_stride = (N / 128) * (K / 128);
+    p.q_out = q; p.s_out = s; p.ldq = ldq; p.sor = sor; p.sok = sok; p.q_pow2 = pow2 ? 1 : 0;
+    return launch_gemm_swiglu_quant(p, pow2, static_cast<hipStream_t>(stream));
+}
+
+ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t inter,
+                                                int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                                                int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
+                                                const float* sb, uint8_t* q, int64_t ldq, float* s, int64_t s_stride_row,
+                                                int64_t s_stride_kb, void* stream) {
+    return grouped_swiglu_quant(false, G, group_offsets, total_rows, inter, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
+                                sb, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+
+ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t inter,
+                                                     int64_t K, const uint8_t* a, int64_t lda, const float* sa,
+                                                     int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b,
+                                                     int64_t ldb, const float* sb, uint8_t* q, int64_t ldq, float* s,
+                                                     int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+    return grouped_swiglu_quant(true, G, group_offsets, total_rows, inter, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
+                                sb, q, ldq, s, s_stride_row, s_stride_kb, stream);
+}
+
 int ds3_gemm_num_variants(void) { return gemm_num_variants(); }
 
 size_t ds3_gemm_workspace_bytes_v(int variant, int64_t M, int64_t N, int64_t K, ds3_bscale sb_mode) {

@@ -103,7 +103,7 @@ struct TileCtx {
 // (one scale per lane and operand: the weight row's and the activation row's);
 // the accumulators then chain through the matrix pipe across K-steps and the
 // vector ALU does no rescaling at all.
-template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2, bool SWIQ = false>
 __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) {
     constexpr int BN = C::BN, BM = C::BM, NT = C::NT, FN = C::FN, FM = C::FM, STAGE = C::STAGE, NSUB = C::NSUB;
     __shared__ __attribute__((aligned(1024))) uint8_t smem[C::LDS_BYTES];
@@ -243,6 +243,14 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
             const int row_lo = min(p.group_offsets[grp], p.M);
             m0 = row_lo + (r % nt_g) * BM;
             m_end = min(p.group_offsets[grp + 1], p.M);
+            // The same for every lane, but read through vector registers (LDS, an indexed global
+            // load): said to be uniform here, the tile's buffer descriptors live in scalar registers.
+            // Left in vector registers, every load of the K-loop would sit in a loop of its own that
+            // picks the descriptor lane by lane, cutting the K-step's instruction schedule to pieces.
+            grp = __builtin_amdgcn_readfirstlane(grp);
+            n0 = __builtin_amdgcn_readfirstlane(n0);
+            m0 = __builtin_amdgcn_readfirstlane(m0);
+            m_end = __builtin_amdgcn_readfirstlane(m_end);
         }
         c.m0 = m0; c.n0 = n0;
         c.m_rows = min(m_end - m0, BM);                // valid rows of this tile (>= 1)
@@ -504,6 +512,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 if (i == 0 && j + 1 < FM) qf[(j + 1) & 1] = load_frag(st + q_base + (j + 1) * 2048);
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(pf[i], qf[j & 1], acc[i][j], 0, 0, 0, ea[i],
                                                                              0, eb[j]);
+                asm volatile("" : "+v"(acc[i][j]));        // ties the MFMA to this point of the K-step
                 if (j == FM - 1) {
                     pf[i] = load_frag(nst + p_base + i * 2048);
 #pragma unroll
@@ -651,6 +660,12 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         // wave instead transposes 16 rows x TN columns at a time through a private
         // LDS strip in the last stage and writes 16 bytes per lane, a full 128-byte (BF16)
         // or 256-byte (FP32) row segment per group of lanes.
+        // Every address of the epilogue derives from this copy of the thread index, which the
+        // compiler cannot see through: none of them is computed before the K-loop and kept in a
+        // register across it (the loop has none to spare).
+        int tid_e = threadIdx.x;
+        asm volatile("" : "+v"(tid_e));
+        const int lane = tid_e & 63, l16 = tid_e & 15, g4 = (tid_e >> 4) & 3;
         constexpr int ESZ = OUT_BF16 ? 2 : 4;
         constexpr int SEG = C::TN * ESZ;                   // bytes of one output row segment of this wave
         constexpr int ROWB = SEG + 16;                     // padded LDS row
@@ -764,7 +779,70 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
                 }
             }
         };
-        if (active) {
+        // SwiGLU and the 1x128 quantiser of the following Linear's input on the tile itself
+        // (Section 3.3.2 fuses the cast with the activation; here both ride on the GEMM that
+        // produces their input).  The weight is stored with gate and up rows interleaved in
+        // blocks of 128, so the 256 columns of a tile are the gate (first 128) and the up
+        // projection (last 128) of the same 128 output columns: one 1x128 tile per row.
+        // The accumulators are rounded to BF16 exactly as the unfused GEMM would store them
+        // and pass through the last code stage, 128 rows at a time; then 16 lanes take one
+        // row (8 columns each), as the stand-alone fused kernel does, with the same
+        // expressions, so the two paths agree bit for bit.
+        auto swiglu_quant_out = [&]() {
+            static_assert(!SWIQ || (C::BN == 256 && C::WM == 2 && NT == 512 && C::TM * 512 <= STAGE), "SwiGLU epilogue shape");
+            uint8_t* hs = smem + (NS - 1) * STAGE;         // [TM rows][256 BF16], 16-byte chunks XOR-swizzled by row
+            const int64_t ob = cur.n0 >> 8;                // this tile's 1x128 tile of the output
+            const int tid = tid_e, lane16 = l16;
+            const int npass = cur.m_rows > C::TM ? 2 : 1;
+            auto lds_barrier = [&]() {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0) only: the next tile's first loads stay in flight
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            };
+            for (int ps = 0; ps < npass; ++ps) {
+                if (wm == ps) {
+#pragma unroll
+                    for (int j = 0; j < FM; ++j) {
+#pragma unroll
+                        for (int i = 0; i < FN; ++i) {
+                            const f32x4 v = acc[i][j];
+                            const int col = wn * C::TN + i * 16 + g4 * 4;
+                            uint8_t* dst = hs + (j * 16 + l16) * 512 + (((col >> 3) ^ l16) << 4) + (col & 7) * 2;
+                            *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+                        }
+                    }
+                }
+                lds_barrier();
+#pragma unroll
+                for (int it = 0; it < C::TM / 32; ++it) {
+                    const int row = it * 32 + (tid >> 4);
+                    const uint8_t* hr = hs + row * 512;
+                    const u32x4 gg = *reinterpret_cast<const u32x4*>(hr + ((lane16 ^ (row & 15)) << 4));
+                    const u32x4 uu = *reinterpret_cast<const u32x4*>(hr + (((16 + lane16) ^ (row & 15)) << 4));
+                    const unsigned int gw[4] = {gg.x, gg.y, gg.z, gg.w}, uw[4] = {uu.x, uu.y, uu.z, uu.w};
+                    unsigned int w[4], m = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        w[e] = pack_bf16x2(silu_mul(bf16_lo(gw[e]), bf16_lo(uw[e])), silu_mul(bf16_hi(gw[e]), bf16_hi(uw[e])));
+                        m = umax(m, umax(w[e] & 0x7fff0000u, (w[e] << 16) & 0x7fff0000u));
+                    }
+                    m = row16_max_bits(m);
+                    const GroupScale gs = group_scale(as_f32(m), p.q_pow2);
+                    const int ml = ps * C::TM + row;
+                    if (ml < cur.m_rows) {
+                        const int64_t grow = cur.m0 + ml;
+                        const u32x2 cw = {cvt4_e4m3(bf16_lo(w[0]) * gs.r, bf16_hi(w[0]) * gs.r, bf16_lo(w[1]) * gs.r, bf16_hi(w[1]) * gs.r),
+                                          cvt4_e4m3(bf16_lo(w[2]) * gs.r, bf16_hi(w[2]) * gs.r, bf16_lo(w[3]) * gs.r, bf16_hi(w[3]) * gs.r)};
+                        __builtin_nontemporal_store(cw, reinterpret_cast<u32x2*>(p.q_out + grow * p.ldq + ob * 128 + lane16 * 8));
+                        if (lane16 == 0) p.s_out[grow * p.sor + ob * p.sok] = gs.s;
+                    }
+                }
+                if (ps + 1 < npass) lds_barrier();         // the second half's rows replace the first's
+            }
+        };
+        if constexpr (SWIQ) swiglu_quant_out();
+        else if (active) {
             if constexpr (GROUPED) write_out(std::false_type{});
             else if (reduce) write_out(std::true_type{});
             else write_out(std::false_type{});
@@ -827,7 +905,7 @@ static size_t share_bytes(int64_t ntiles, int64_t slots, int kb, int* q_main, in
     return *tail_max ? kCounterBytes + (size_t)8 * *tail_max * 2 * C::BN * C::BM * sizeof(float) : 0;
 }
 
-template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2>
+template <class C, bool ROWSB, bool OUT_BF16, bool GROUPED, bool POW2, bool SWIQ = false>
 static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws_need, hipStream_t st) {
     if (GROUPED) p.tiles_m = (p.M + C::BM - 1) / C::BM + p.G;
     else p.tiles_m = (p.M + C::BM - 1) / C::BM;
@@ -859,7 +937,7 @@ static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws
         const int kb = p.K / 128;
         p.share_skew = (2 * q_main == kb && (q_last == 0 || q_last == q_main) && q_main > kShareSkew + 2) ? kShareSkew : 0;
     }
-    gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED, POW2><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
+    gemm_fp8_bs_kernel<C, ROWSB, OUT_BF16, GROUPED, POW2, SWIQ><<<dim3(grid), dim3(C::NT), 0, st>>>(p);
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
 
@@ -902,6 +980,13 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
     if (variant < 0) variant = default_variant(p, mode);
     return pow2 ? launch_variant<true>(p, ct, mode, variant, ws, ws_bytes, nullptr, st)
                 : launch_variant<false>(p, ct, mode, variant, ws, ws_bytes, nullptr, st);
+}
+
+ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, hipStream_t st) {
+    using C = Cfg<256, 256, 4, 2, 2>;                   // a tile holds the gate and the up half of one 1x128 output tile
+    if (p.G <= 0 || p.N % 256) return DS3_ERR_SHAPE;
+    return pow2 ? launch_one<C, false, true, true, true, true>(p, nullptr, 0, nullptr, st)
+                : launch_one<C, false, true, true, false, true>(p, nullptr, 0, nullptr, st);
 }
 
 __global__ void zero_fill_kernel(uint8_t* c, int64_t row_bytes, int64_t ld_bytes, int64_t rows) {

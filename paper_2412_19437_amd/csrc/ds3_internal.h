@@ -59,6 +59,11 @@ struct GemmParams {
     int share_tail_max;    // most shared tiles any XCD has
     int share_steps, share_steps_last;   // K-steps per workgroup in a shared tail (XCDs with a full chunk / the last one)
     int share_skew;        // K-steps moved from the odd workgroups' runs to the even ones'
+    // SwiGLU + 1x128 quantisation in the epilogue (grouped gate|up projection only; c is unused then)
+    uint8_t* q_out;        // [M][ldq] codes of the activation
+    float* s_out;          // scales, element (row, 1x128 tile t) at s_out[row * sor + t * sok]
+    int64_t ldq, sor, sok;
+    int q_pow2;            // scales of the activation rounded up to powers of two
 };
 
 // variant: which tile configuration to run (see ds3_gemm.hip); -1 = choose by shape.
@@ -69,6 +74,9 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
 // As launch_gemm with the library's own statically allocated workspace (one per device).
 ds3_status launch_gemm_static_scratch(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int variant, bool pow2, hipStream_t st);
 size_t gemm_static_scratch_bytes();
+// Grouped GEMM over a gate|up weight interleaved in blocks of 128 rows, with SwiGLU and the 1x128
+// quantiser of the following Linear's input applied to each tile before it leaves the chip.
+ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, hipStream_t st);
 // Bytes of workspace with which launch_gemm shares tail tiles for this shape (0: it would not).
 size_t gemm_workspace_bytes(const GemmParams& p, ds3_bscale mode, int variant);
 // K-steps per workgroup for a shared tail (see ds3_gemm.hip); host logic, exported for its test.

@@ -136,6 +136,19 @@ def cfg3_w2(g=LOCAL_EXPERTS, inter=MOE_INTER, k=HIDDEN):
 
 
 # ---- config 4: backward of the config-2 layer -------------------------------
+def interleave_gate_up(t: np.ndarray, block: int = 128) -> np.ndarray:
+    """Row order of the fused gate|up weight for the GEMM whose epilogue applies SwiGLU:
+    [..., 2*I, ...] with gate rows [0, I) and up rows [I, 2I) on axis -2 becomes
+    gate block 0, up block 0, gate block 1, up block 1, ... in blocks of `block` rows.
+    Used with block = 128 on the codes and block = 1 on their 128x128 scales."""
+    two_i = t.shape[-2]
+    nb = two_i // 2 // block
+    assert two_i == 2 * nb * block
+    lead, tail = t.shape[:-2], t.shape[-1:]
+    v = t.reshape(*lead, 2, nb, block, *tail)
+    return np.ascontiguousarray(np.swapaxes(v, -4, -3)).reshape(t.shape)
+
+
 def cfg4_dy(m=4096, n=DENSE_INTER):
     return normal((m, n), 1e-2, seed_for(4, 0))
 

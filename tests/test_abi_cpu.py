@@ -171,6 +171,20 @@ def test_later_entry_points_reject_bad_arguments_on_the_host(pkg):
     assert sq(p, 4, 12, 24, p, 16, p, 1, 4, None) == 3                        # inter % 8
     assert sq(p, 4, 16, 24, p, 16, p, 1, 4, None) == 2                        # ldh < 2 * inter
     assert sq(p, 4, 16, 32, None, 16, p, 1, 4, None) == 1
+    for gq in (L.ds3_grouped_gemm_swiglu_quant_fp8_bs, L.ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2):
+        ok = (2, p, 32, 128, 128, p, 128, p, 1, 32, p, 128, p, p, 128, p, 1, 32, None)
+
+        def with_(i, v):
+            return ok[:i] + (v,) + ok[i + 1:]
+        assert gq(*with_(3, 64)) == 2                                         # inter % 128
+        assert gq(*with_(4, 100)) == 2                                        # K % 128
+        assert gq(*with_(4, 0)) == 2                                          # K == 0
+        assert gq(*with_(14, 64)) == 2                                        # ldq < inter
+        assert gq(*with_(14, 136)) == 3                                       # ldq % 16
+        assert gq(*with_(13, None)) == 1 and gq(*with_(15, None)) == 1        # outputs missing
+        assert gq(*with_(1, None)) == 1 and gq(*with_(10, None)) == 1         # offsets, weight missing
+        assert gq(*with_(0, 0)) == 0 and gq(*with_(2, 0)) == 0                # nothing to do
+        assert gq(*with_(0, -1)) == 2 and gq(*with_(0, 1024)) == 5
     rn = L.ds3_rmsnorm_quant_1x128
     assert rn(p, 4, 128, 128, None, 1e-6, None, 0, p, 128, p, 1, 4, None) == 1      # gamma missing
     assert rn(p, 4, 8200, 8200, p, 1e-6, None, 0, p, 8208, p, 1, 4, None) == 5      # row longer than 8192
