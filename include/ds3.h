@@ -380,9 +380,9 @@ ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inte
  *   q   [total_rows][ldq] codes of silu(gate) * up, `inter` valid columns
  *   s   scales of q, element (row, tile t) at s[row * s_stride_row + t * s_stride_kb]
  * inter % 128 == 0, K > 0; q 16-byte aligned, ldq % 16 == 0, ldq >= inter.
- * Result: bit for bit that of ds3_grouped_gemm_fp8_bs (BF16 output, tile
- * configuration 0) on the same operands followed by ds3_swiglu_quant_1x128
- * on its de-interleaved output.  The _pow2 form takes operands whose scales
+ * Result: bit for bit that of ds3_grouped_gemm_fp8_bs (BF16 output) on the
+ * same operands followed by ds3_swiglu_quant_1x128 on its de-interleaved
+ * output.  The _pow2 form takes operands whose scales
  * are all powers of two and writes power-of-two scales.
  * Rows at or beyond group_offsets[G] are left untouched.
  */

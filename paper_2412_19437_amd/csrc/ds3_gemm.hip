@@ -966,10 +966,12 @@ static ds3_status launch_variant(const GemmParams& p, ds3_dtype ct, ds3_bscale m
 
 // The tile configuration a shape runs with when the caller does not name one.
 static int default_variant(const GemmParams& p, ds3_bscale mode) {
-    // the 256x256 tile (also the fastest for the ragged expert groups); the per-row-scale
-    // form (more live registers) takes the narrower M tile; problems with too few large
-    // tiles to fill the chip take 128x128 tiles, two workgroups per CU
-    int variant = (mode == DS3_BSCALE_PER_ROW) ? 1 : 0;
+    // the 256x256 tile; the ragged expert groups take 256x128 tiles in three stages (their
+    // weights come from HBM, not from the L2, and want the deeper prefetch; 128-row tiles
+    // also pad less); problems with too few large tiles to fill the chip take 128x128 tiles,
+    // two workgroups per CU
+    (void)mode;
+    int variant = p.G > 0 ? 1 : 0;
     const int64_t big = (int64_t)((p.M + 255) / 256) * ((p.N + 255) / 256);
     if (p.G == 0 && big * 8 < 5 * (int64_t)num_cus_x8()) variant = 2;
     return variant;
@@ -983,7 +985,9 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
 }
 
 ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, hipStream_t st) {
-    using C = Cfg<256, 256, 4, 2, 2>;                   // a tile holds the gate and the up half of one 1x128 output tile
+    // 256 weight rows per tile: the gate and the up half of one 1x128 output tile; 128 activation
+    // rows and three stages, as the plain grouped GEMM runs by default
+    using C = Cfg<256, 128, 4, 2, 3>;
     if (p.G <= 0 || p.N % 256) return DS3_ERR_SHAPE;
     return pow2 ? launch_one<C, false, true, true, true, true>(p, nullptr, 0, nullptr, st)
                 : launch_one<C, false, true, true, false, true>(p, nullptr, 0, nullptr, st);
