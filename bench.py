@@ -41,6 +41,8 @@ def parse():
                     help="bracket the kernels with HIP events on every n-th timed step only (1 = every step)")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "fused"])
     ap.add_argument("--unfused-swiglu", action="store_true", help="cfg3: separate SwiGLU and 1x128 quantizer kernels")
+    ap.add_argument("--swiglu-kernel", action="store_true",
+                    help="cfg3: SwiGLU and the 1x128 quantizer as one kernel behind the gate|up GEMM (default: in its epilogue)")
     ap.add_argument("--wgrad-from-cache", action="store_true",
                     help="cfg4: the Wgrad activation operand is re-tiled from the FP8 1x128 cache instead of re-quantized from BF16")
     ap.add_argument("--dual-weight-quant", action="store_true",
@@ -88,11 +90,11 @@ def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
     """Dense FFN up-projection Fprop.  Two input sets are rotated so that the
     quantizers stream from HBM rather than from the 256 MB last-level cache."""
     M, N, K = 4096, wl.DENSE_INTER, wl.HIDDEN
-    nsets = 2
+    nsets_x, nsets_w = 10, 3                     # 587 MB of X, 793 MB of W: more than twice the last-level cache each
     x = wl.cfg2_x()
     w = wl.cfg2_w()
-    xs = [torch.from_numpy(x).to(dev).to(torch.bfloat16) for _ in range(nsets)]
-    ws = [torch.from_numpy(w).to(dev).to(torch.bfloat16) for _ in range(nsets)]
+    xs = [torch.from_numpy(x).to(dev).to(torch.bfloat16) for _ in range(nsets_x)]
+    ws = [torch.from_numpy(w).to(dev).to(torch.bfloat16) for _ in range(nsets_w)]
     del x, w
     state = {"i": 0}
     qa, sa = (ds3.ds3_quant_act_1x128_pow2 if pow2 else ds3.ds3_quant_act_1x128)(xs[0])
@@ -105,11 +107,11 @@ def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
     c_gemm = L.ds3_gemm_fp8_bs_pow2 if pow2 else L.ds3_gemm_fp8_bs_v
 
     def quant_x():
-        xi = xs[state["i"] % nsets]
+        xi = xs[state["i"] % nsets_x]
         c_quant_x(xi.data_ptr(), ds3.DS3_BF16, M, K, K, qa.data_ptr(), K, sa.data_ptr(), sa.stride(0), sa.stride(1), st)
 
     def quant_w():
-        wi = ws[state["i"] % nsets]
+        wi = ws[state["i"] % nsets_w]
         c_quant_w(wi.data_ptr(), ds3.DS3_BF16, N, K, K, qb.data_ptr(), K, sb.data_ptr(), st)
 
     def gemm():
@@ -254,7 +256,7 @@ def main():
         import bench_extra
         step, kernels, flops, cfg, dominant = bench_extra.build(args.workload, ds3, torch, wl, dev, args.gemm_variant,
                                                                 args.pow2, args.unfused_swiglu, args.wgrad_from_cache,
-                                                                args.dual_weight_quant)
+                                                                args.dual_weight_quant, args.swiglu_kernel)
     else:
         step, kernels, flops, cfg, dominant = build_cfg2(ds3, torch, wl, dev, args.gemm_variant, args.pow2)
 

@@ -23,6 +23,7 @@ def _quant_bytes(rows, cols, groups):
 
 
 _UNFUSED_SWIGLU = False
+_SWIGLU_KERNEL = False
 _WGRAD_FROM_CACHE = False
 _DUAL_WEIGHT_QUANT = False
 
@@ -34,16 +35,18 @@ class _Pow2:
         self._ds3 = ds3
 
     def __getattr__(self, name):
-        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_swiglu_quant", "ds3_retile_")) \
+        if name.startswith(("ds3_quant_", "ds3_gemm_fp8_bs", "ds3_grouped_gemm_fp8_bs", "ds3_grouped_gemm_swiglu_quant_fp8_bs",
+                            "ds3_swiglu_quant", "ds3_retile_")) \
                 and not name.endswith("_pow2"):
             return getattr(self._ds3, name + "_pow2")
         return getattr(self._ds3, name)
 
 
 def build(workload, ds3, torch, wl, dev, variant, pow2=False, unfused_swiglu=False, wgrad_from_cache=False,
-          dual_weight_quant=False):
-    global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT
+          dual_weight_quant=False, swiglu_kernel=False):
+    global _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT, _SWIGLU_KERNEL
     _UNFUSED_SWIGLU, _WGRAD_FROM_CACHE, _DUAL_WEIGHT_QUANT = unfused_swiglu, wgrad_from_cache, dual_weight_quant
+    _SWIGLU_KERNEL = swiglu_kernel
     step, kernels, flops, cfg, dominant = {"cfg3": _cfg3, "cfg4": _cfg4, "cfg5": _cfg5, "fused": _fused}[workload](
         _Pow2(ds3) if pow2 else ds3, torch, wl, dev, variant)
     if pow2:
@@ -58,7 +61,9 @@ def _bf16(torch, x, dev):
 
 def _cfg3(ds3, torch, wl, dev, variant):
     """MoE expert FFN forward of one GPU's 32 experts: quant 1x128 -> grouped
-    gate|up GEMM -> SwiGLU -> quant 1x128 -> grouped down GEMM."""
+    gate|up GEMM -> SwiGLU -> quant 1x128 -> grouped down GEMM.  By default the
+    middle three run as one kernel (SwiGLU and the cast in the GEMM's epilogue,
+    on a gate|up weight interleaved in blocks of 128 rows)."""
     Timed = _timed()
     G, H, I = wl.LOCAL_EXPERTS, wl.HIDDEN, wl.MOE_INTER
     sizes, off, _ = wl.cfg3_routing()
@@ -72,6 +77,11 @@ def _cfg3(ds3, torch, wl, dev, variant):
     q2, s2 = ds3.ds3_quant_w_128x128(w2)
     q13v, s13v = q13.view(G, 2 * I, H), s13.view(G, 2 * I // 128, H // 128)
     q2v, s2v = q2.view(G, H, I), s2.view(G, H // 128, I // 128)
+    in_gemm = not (_UNFUSED_SWIGLU or _SWIGLU_KERNEL)
+    if in_gemm:
+        # whole 128-row blocks move: the interleaved weight's codes and scales are those of w13, reordered
+        q13i = q13v.view(G, 2, I // 128, 128, H).transpose(1, 2).contiguous().view(G, 2 * I, H)
+        s13i = s13v.view(G, 2, I // 128, H // 128).transpose(1, 2).contiguous().view(G, 2 * I // 128, H // 128)
     st = {}
 
     def quant_x():
@@ -93,6 +103,9 @@ def _cfg3(ds3, torch, wl, dev, variant):
     def swiglu_quant():
         st["qh"], st["sh"] = ds3.ds3_swiglu_quant_1x128(st["h"])
 
+    def gemm1_swiglu_quant():
+        st["qh"], st["sh"] = ds3.ds3_grouped_gemm_swiglu_quant_fp8_bs(st["qx"], st["sx"], offd, q13i, s13i)
+
     def gemm2():
         st["y"] = ds3.ds3_grouped_gemm_fp8_bs(st["qh"], st["sh"], offd, q2v, s2v, variant=variant)
 
@@ -106,11 +119,18 @@ def _cfg3(ds3, torch, wl, dev, variant):
         Timed("quant_act_1x128(h)", quant_h, "GB/s", _quant_bytes(rows, I, rows * I // 128) / 1e9, "hbm", PEAK_HBM_GBS),
         Timed("grouped_gemm_fp8_bs(down)", gemm2, "TFLOP/s", f2 / 1e12, "mfma", PEAK_FP8_TFLOPS),
     ]
-    if not _UNFUSED_SWIGLU:
+    dominant = "grouped_gemm_fp8_bs(gate|up)"
+    if in_gemm:
+        dominant = "grouped_gemm_swiglu_quant_fp8_bs(gate|up)"
+        kernels = kernels[:2] + [Timed(dominant, gemm1_swiglu_quant, "TFLOP/s", f1 / 1e12, "mfma", PEAK_FP8_TFLOPS)] + kernels[5:]
+    elif _SWIGLU_KERNEL:
         # one pass: reads the gate|up output (4 B per activation), writes codes + scales (1.03 B)
         fused = Timed("swiglu_quant_1x128(fused)", swiglu_quant, "GB/s", (rows * I * 5 + rows * I // 128 * 4) / 1e9, "hbm",
                       PEAK_HBM_GBS)
         kernels = kernels[:3] + [fused] + kernels[5:]
+    # rows the GEMM tiles cover / rows that hold tokens (128-row tiles unless a 256-row variant is forced)
+    bm = 256 if variant == 0 else 128
+    padded = int(sum((int(n) + bm - 1) // bm * bm for n in sizes))
 
     def step(record):
         for k in kernels:
@@ -118,10 +138,13 @@ def _cfg3(ds3, torch, wl, dev, variant):
 
     cfg = {"workload": "cfg3: MoE grouped Fprop, 32 local experts of 256, 8192 tokens top-8 (sigmoid affinity + bias), "
                        "gate|up [n_e x 7168]x[4096x7168]^T, SwiGLU, down [n_e x 2048]x[7168x2048]^T, BF16 out",
-           "swiglu": "separate SwiGLU and quantizer kernels" if _UNFUSED_SWIGLU else "fused with the 1x128 quantizer",
+           "swiglu": ("separate SwiGLU and quantizer kernels" if _UNFUSED_SWIGLU else
+                      "one kernel with the 1x128 quantizer" if _SWIGLU_KERNEL else
+                      "in the gate|up GEMM's epilogue together with the 1x128 quantizer"),
+           "padding_efficiency": rows / padded, "tile_rows": bm,
            "rows": rows, "group_sizes_min_med_max": [int(sizes.min()), int(np.median(sizes)), int(sizes.max())],
            "gemm_variant": variant}
-    return step, kernels, f1 + f2, cfg, "grouped_gemm_fp8_bs(gate|up)"
+    return step, kernels, f1 + f2, cfg, dominant
 
 
 def _cfg4(ds3, torch, wl, dev, variant):
