@@ -66,7 +66,12 @@ def _moe_pipeline(ds3, sizes, off, sampled, ids=None, tag="cfg3"):
             continue
         picks[e] = np.unique(np.concatenate([[lo, hi - 1, min(lo + 255, hi - 1), min(lo + 256, hi - 1)], rng.integers(lo, hi, 4)]))
         _check_bf16(f"{tag} gate|up expert {e} ({hi - lo} rows)", h_h[picks[e]], qx_h[picks[e]], sx_h[picks[e]], host(q13v[e]), host(s13v[e]))
-    del q13, s13, q13v, s13v
+    # the same projection with SwiGLU and the cast in its epilogue (gate|up rows interleaved in
+    # blocks of 128): compared below with the codes the two separate kernels give
+    q13i = q13v.view(G, 2, I // 128, 128, H).transpose(1, 2).contiguous().view(G, 2 * I, H)
+    s13i = s13v.view(G, 2, I // 128, H // 128).transpose(1, 2).contiguous().view(G, 2 * I // 128, H // 128)
+    qh_e, sh_e = ds3.ds3_grouped_gemm_swiglu_quant_fp8_bs(qx, sx, dev(off), q13i, s13i)
+    del q13, s13, q13v, s13v, q13i, s13i
     # SwiGLU fused with the 1x128 quantizer, on the GPU's own H.  Staged parity: the activation
     # ds3_swiglu writes is within one BF16 ulp of the FP64 SwiGLU of H, and the fused kernel's codes
     # and scales equal, bit for bit, the oracle's quantization of that BF16 activation (the codes
@@ -80,6 +85,9 @@ def _moe_pipeline(ds3, sizes, off, sampled, ids=None, tag="cfg3"):
     qh_ref, sh_ref = orc.quant_act_1x128(act)
     assert np.array_equal(host(qh), qh_ref), f"{tag}: fused SwiGLU->quant codes"
     assert np.array_equal(host(sh), sh_ref), f"{tag}: fused SwiGLU->quant scales"
+    assert np.array_equal(host(qh_e)[:rows], qh_ref), f"{tag}: SwiGLU->quant in the GEMM epilogue, codes"
+    assert np.array_equal(host(sh_e)[:rows], sh_ref), f"{tag}: SwiGLU->quant in the GEMM epilogue, scales"
+    del qh_e, sh_e
     q_all, s_all = orc.swiglu_quant_1x128(h_h)
     assert np.mean(qh_ref == q_all) > 0.98 and np.mean(sh_ref == s_all) > 0.9
     del act, ref_act, ulp, q_all, s_all
