@@ -61,9 +61,10 @@ def parse():
 class Timed:
     """A kernel launch bracketed by HIP events on the launching (current) stream."""
 
-    def __init__(self, name, fn, unit, work, bound, peak):
+    def __init__(self, name, fn, unit, work, bound, peak, also=None):
         import torch
         self.name, self.fn, self.unit, self.work, self.bound, self.peak = name, fn, unit, work, bound, peak
+        self.also = also                         # (bound, unit, work, peak): the kernel against its other roofline
         self.pairs = []
         self._torch = torch
 
@@ -82,8 +83,12 @@ class Timed:
         ms = sorted(a.elapsed_time(b) for a, b in self.pairs)
         avg = sum(ms) / len(ms)
         achieved = self.work / (avg * 1e-3)
-        return dict(name=self.name, avg_us=avg * 1e3, min_us=ms[0] * 1e3, bound=self.bound, achieved=achieved,
-                    peak=self.peak, unit=self.unit, frac=achieved / self.peak)
+        out = dict(name=self.name, avg_us=avg * 1e3, min_us=ms[0] * 1e3, bound=self.bound, achieved=achieved,
+                   peak=self.peak, unit=self.unit, frac=achieved / self.peak)
+        if self.also:
+            b, u, w, pk = self.also
+            out["also"] = dict(bound=b, unit=u, achieved=w / (avg * 1e-3), peak=pk, frac=w / (avg * 1e-3) / pk)
+        return out
 
 
 def build_cfg2(ds3, torch, wl, dev, variant, pow2=False):
