@@ -218,8 +218,8 @@ ds3_status ds3_grouped_gemm_fp8_bs_v(int variant, int32_t G, const int32_t* grou
 
 /*
  * Power-of-two scaling factors (Section 3.3.3: the inputs of the Linear after
- * attention and the activations quantized before MoE dispatch use factors that
- * are integral powers of two).  The three quantizers with
+ * attention and the activations quantized before MoE dispatch use factors of
+ * the form 2^e, e an integer).  The three quantizers with
  *         s = the smallest power of two >= amax / 448     (1 if amax == 0)
  *         r = 1 / s (exact),   q_i = E4M3_round_to_nearest_even(x_i * r)
  * in place of the rule at the top of this file; arguments, layouts and
@@ -306,7 +306,7 @@ ds3_status ds3_swiglu(const void* h, int64_t rows, int64_t inter, int64_t ldh,
  * operand of Dgrad (Section 3.3.1: dX = dY W contracts over W's rows; the
  * 128x128 blocks and their scales are transpose-invariant, so W^T needs no
  * second quantization -- Appendix B.2 makes the same point for block-wise
- * tiles: "only transposition is required").  One read of W, two layouts:
+ * tiles).  One read of W, two layouts:
  *   q    [n][ldq]   and  s    [ceil(n/128)][ceil(k/128)]   as ds3_quant_w_128x128
  *   q_t  [k][ldqt]  and  s_t  [ceil(k/128)][ceil(n/128)]:  q_t[c][r] = q[r][c], s_t[j][i] = s[i][j]
  * Alignment as ds3_quant_w_128x128, plus q_t 16-byte aligned and ldqt % 16 == 0.

@@ -23,7 +23,7 @@ What it follows (DeepSeek-V3 technical report, arXiv 2412.19437):
 
 Readings where the paper is silent:
 
-* "maximum representable value of FP8" = 448, the OCP E4M3 maximum.
+* the largest FP8 value that a group's max-abs is mapped to (Section 3.3.2) = 448, the OCP E4M3 maximum.
 * The stored factor is the de-quantisation scale  s = fl32(amax / 448).
 * Elements are scaled by one FP32 multiply with r = fl32(448 / amax), then
   rounded to nearest-even onto the E4M3 grid; magnitudes that would round

@@ -25,8 +25,8 @@ pytestmark = pytest.mark.gpu
 #   its root mean square over the outputs                       measured 2.4e-5
 #   normwise      ||C - exact|| / ||exact||                     measured 5.1e-5  -> TOL_F32 = 1e-4 in the GEMM tests
 # The matrix unit keeps about 13 bits below the sum of the magnitudes -- the same order as the
-# "around 14 bits" the report quotes for its hardware; here it applies to ONE 128-element
-# interval, never to a longer sum.
+# roughly 14 bits that Section 3.3.2 reports for the accumulation on its hardware; here it applies
+# to ONE 128-element interval, never to a longer sum.
 BETA = 2.0 ** -11.6
 RMS = 5e-5
 TOL_F32 = 1e-4
