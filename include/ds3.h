@@ -158,7 +158,7 @@ ds3_status ds3_gemm_fp8_bs(int64_t M, int64_t N, int64_t K,
  * a workspace: the same operation, arguments and results as ds3_gemm_fp8_bs with a
  * workspace of ds3_gemm_workspace_bytes() bytes, but the partial sums of shared tiles go
  * through a statically allocated device array of the library
- * (ds3_gemm_noalloc_scratch_bytes() = 76 MiB + 2 KiB, held by every GPU the library is
+ * (ds3_gemm_noalloc_scratch_bytes() = 76 MiB + 2.25 KiB, held by every GPU the library is
  * loaded on until the process ends).  The call allocates and frees nothing.  A shape that
  * would need more than the array holds is refused with DS3_ERR_WORKSPACE (no shape does on
  * a device of up to 256 compute units).  All calls on one GPU share the array: calls that
@@ -266,18 +266,24 @@ ds3_status ds3_grouped_gemm_fp8_bs_pow2(int variant, int32_t G, const int32_t* g
  * Bytes of device workspace with which ds3_gemm_fp8_bs / _pow2 share tail tiles
  * along K for this shape (the larger of the two scale modes' needs; 0: the call
  * would not use a workspace).  The _v form answers for one tile configuration
- * and scale mode (variant -1: the default choice).  The grouped calls take no
- * workspace (pass NULL).
+ * and scale mode (variant -1: the default choice).
+ * The grouped calls use a workspace of ds3_grouped_gemm_workspace_bytes() bytes
+ * (a few counters, any shape): with it the tiles beyond each workgroup's first
+ * are handed out through a queue, so workgroups that drew tiles with few valid
+ * rows take more of them (the results do not depend on it, bit for bit); with
+ * NULL the walk is static.  One workspace serves dense and grouped calls alike,
+ * under the same rules (prepared once, not shared by overlapping calls).
  */
 size_t ds3_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t ds3_gemm_workspace_bytes_v(int variant, int64_t M, int64_t N, int64_t K, ds3_bscale sb_mode);
+size_t ds3_grouped_gemm_workspace_bytes(void);
 
 /*
  * Prepares a freshly allocated workspace (enqueues a small kernel that zeroes
  * the arrival counters at its head; the rest needs no initialisation).  Once
  * per allocation: the GEMM calls leave the counters as they need them.
- * workspace_bytes == 0 is a no-op; a non-zero size below the counters' 2 KiB is
- * DS3_ERR_WORKSPACE.
+ * workspace_bytes == 0 is a no-op; a non-zero size below that of the counters
+ * (ds3_grouped_gemm_workspace_bytes()) is DS3_ERR_WORKSPACE.
  */
 ds3_status ds3_gemm_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
@@ -384,7 +390,8 @@ ds3_status ds3_swiglu_quant_1x128_pow2(const void* h, int64_t rows, int64_t inte
  * same operands followed by ds3_swiglu_quant_1x128 on its de-interleaved
  * output.  The _pow2 form takes operands whose scales
  * are all powers of two and writes power-of-two scales.
- * Rows at or beyond group_offsets[G] are left untouched.
+ * Rows at or beyond group_offsets[G] are left untouched.  workspace as in
+ * ds3_grouped_gemm_fp8_bs.
  */
 ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows,
                                                 int64_t inter, int64_t K,
@@ -392,14 +399,16 @@ ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs(int32_t G, const int32_t* group_
                                                 const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
                                                 const uint8_t* b, int64_t ldb, const float* sb,
                                                 uint8_t* q, int64_t ldq,
-                                                float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+                                                float* s, int64_t s_stride_row, int64_t s_stride_kb,
+                                                void* workspace, size_t workspace_bytes, void* stream);
 ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(int32_t G, const int32_t* group_offsets, int64_t total_rows,
                                                      int64_t inter, int64_t K,
                                                      const uint8_t* a, int64_t lda,
                                                      const float* sa, int64_t sa_stride_row, int64_t sa_stride_kb,
                                                      const uint8_t* b, int64_t ldb, const float* sb,
                                                      uint8_t* q, int64_t ldq,
-                                                     float* s, int64_t s_stride_row, int64_t s_stride_kb, void* stream);
+                                                     float* s, int64_t s_stride_row, int64_t s_stride_kb,
+                                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * RMSNorm fused with the 1x128 quantization of its output, the input of the

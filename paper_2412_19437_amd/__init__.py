@@ -33,6 +33,7 @@ SYMBOLS = [
     "ds3_rmsnorm_quant_1x128", "ds3_rmsnorm_quant_1x128_pow2", "ds3_adamw_bf16_states",
     "ds3_quant_act_1x128_e5m6", "ds3_dequant_e5m6",
     "ds3_grouped_gemm_swiglu_quant_fp8_bs", "ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2",
+    "ds3_grouped_gemm_workspace_bytes",
 ]
 
 
@@ -67,7 +68,10 @@ def _load() -> ctypes.CDLL:
     lib.ds3_swiglu.argtypes = [vp, i64, i64, i64, vp, i64, vp]
     lib.ds3_swiglu_quant_1x128.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     for name in ("ds3_grouped_gemm_swiglu_quant_fp8_bs", "ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2"):
-        getattr(lib, name).argtypes = [ctypes.c_int32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i64, vp, i64, i64, vp]
+        getattr(lib, name).argtypes = [ctypes.c_int32, vp, i64, i64, i64, vp, i64, vp, i64, i64, vp, i64, vp, vp, i64, vp, i64, i64,
+                                       vp, ctypes.c_size_t, vp]
+    lib.ds3_grouped_gemm_workspace_bytes.argtypes = []
+    lib.ds3_grouped_gemm_workspace_bytes.restype = ctypes.c_size_t
     lib.ds3_swiglu_quant_1x128_pow2.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
     lib.ds3_retile_1x128_to_128x1_pow2.argtypes = [vp, i64, i64, i64, vp, i64, i64, vp, i64, vp, i64, i64, vp]
@@ -273,19 +277,27 @@ def _gemm(entry, a, sa, b, sb, sb_mode, out_dtype, c, accumulate, variant, works
 
 
 def ds3_grouped_gemm_fp8_bs(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat16,
-                            c: torch.Tensor | None = None, variant: int = -1):
+                            c: torch.Tensor | None = None, variant: int = -1, workspace="auto"):
     """Per expert g: rows [off[g], off[g+1]) of a times b[g] ([G][N][K] codes,
-    sb [G][ceil(N/128)][K/128]).  group_offsets: int32 device tensor of G+1."""
-    return _grouped("ds3_grouped_gemm_fp8_bs_v", a, sa, group_offsets, b, sb, out_dtype, c, variant)
+    sb [G][ceil(N/128)][K/128]).  group_offsets: int32 device tensor of G+1.
+    workspace: "auto" (the cached one: tiles are handed out through a queue), None (static walk)
+    or a prepared uint8 tensor; the result is the same bit for bit."""
+    return _grouped("ds3_grouped_gemm_fp8_bs_v", a, sa, group_offsets, b, sb, out_dtype, c, variant, workspace)
 
 
 def ds3_grouped_gemm_fp8_bs_pow2(a, sa, group_offsets, b, sb, out_dtype=torch.bfloat16,
-                                 c: torch.Tensor | None = None, variant: int = -1):
+                                 c: torch.Tensor | None = None, variant: int = -1, workspace="auto"):
     """As ds3_grouped_gemm_fp8_bs for operands whose scales are all powers of two."""
-    return _grouped("ds3_grouped_gemm_fp8_bs_pow2", a, sa, group_offsets, b, sb, out_dtype, c, variant)
+    return _grouped("ds3_grouped_gemm_fp8_bs_pow2", a, sa, group_offsets, b, sb, out_dtype, c, variant, workspace)
 
 
-def _grouped(entry, a, sa, group_offsets, b, sb, out_dtype, c, variant):
+def _grouped_ws(workspace, device):
+    if isinstance(workspace, str):
+        workspace = gemm_workspace(_L().ds3_grouped_gemm_workspace_bytes(), device)
+    return (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+
+
+def _grouped(entry, a, sa, group_offsets, b, sb, out_dtype, c, variant, workspace="auto"):
     m, k, lda = _rows2d(a, "a")
     g, n, kk = b.shape
     if kk != k or not b.is_contiguous() or not sb.is_contiguous():
@@ -297,7 +309,7 @@ def _grouped(entry, a, sa, group_offsets, b, sb, out_dtype, c, variant):
     _, _, ldc = _rows2d(c, "c")
     st = getattr(_L(), entry)(variant, g, group_offsets.data_ptr(), m, n, k, a.data_ptr(), lda,
                               sa.data_ptr(), sa.stride(0), sa.stride(1), b.data_ptr(), k, sb.data_ptr(),
-                              c.data_ptr(), _dt(c), ldc, None, 0, _stream())
+                              c.data_ptr(), _dt(c), ldc, *_grouped_ws(workspace, a.device), _stream())
     _check(st, entry)
     return c
 
@@ -422,7 +434,7 @@ def ds3_swiglu_quant_1x128_pow2(h: torch.Tensor, k_major_scales: bool = True):
     return _swiglu_quant("ds3_swiglu_quant_1x128_pow2", h, k_major_scales)
 
 
-def _grouped_swiglu_quant(entry, a, sa, group_offsets, b, sb, k_major_scales):
+def _grouped_swiglu_quant(entry, a, sa, group_offsets, b, sb, k_major_scales, workspace="auto"):
     m, k, lda = _rows2d(a, "a")
     g, n, kk = b.shape
     if kk != k or n % 256 or not b.is_contiguous() or not sb.is_contiguous():
@@ -434,22 +446,23 @@ def _grouped_swiglu_quant(entry, a, sa, group_offsets, b, sb, k_major_scales):
     s = _scales(m, inter // 128, a.device, k_major_scales)
     st = getattr(_L(), entry)(g, group_offsets.data_ptr(), m, inter, k, a.data_ptr(), lda, sa.data_ptr(), sa.stride(0),
                               sa.stride(1), b.data_ptr(), k, sb.data_ptr(), q.data_ptr(), inter, s.data_ptr(),
-                              s.stride(0), s.stride(1), _stream())
+                              s.stride(0), s.stride(1), *_grouped_ws(workspace, a.device), _stream())
     _check(st, entry)
     return q, s
 
 
-def ds3_grouped_gemm_swiglu_quant_fp8_bs(a, sa, group_offsets, b, sb, k_major_scales: bool = True):
+def ds3_grouped_gemm_swiglu_quant_fp8_bs(a, sa, group_offsets, b, sb, k_major_scales: bool = True, workspace="auto"):
     """Grouped gate|up projection with SwiGLU and the 1x128 quantizer in its epilogue.
     b: [G][2*inter][K] codes with gate and up rows interleaved in blocks of 128
     (128 gate rows, the 128 up rows of the same range, ...), sb in the same order.
     Returns (codes [rows][inter], scales) of silu(gate) * up; rows beyond the last group are not written."""
-    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs", a, sa, group_offsets, b, sb, k_major_scales)
+    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs", a, sa, group_offsets, b, sb, k_major_scales, workspace)
 
 
-def ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(a, sa, group_offsets, b, sb, k_major_scales: bool = True):
+def ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(a, sa, group_offsets, b, sb, k_major_scales: bool = True, workspace="auto"):
     """As ds3_grouped_gemm_swiglu_quant_fp8_bs: power-of-two scales in, power-of-two scales out."""
-    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2", a, sa, group_offsets, b, sb, k_major_scales)
+    return _grouped_swiglu_quant("ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2", a, sa, group_offsets, b, sb, k_major_scales,
+                                 workspace)
 
 
 def _retile(entry: str, q: torch.Tensor, s: torch.Tensor, k_major_scales: bool):

@@ -211,7 +211,7 @@ ds3_status ds3_grouped_gemm_fp8_bs(int32_t G, const int32_t* group_offsets, int6
 static ds3_status grouped_swiglu_quant(bool pow2, int32_t G, const int32_t* offs, int64_t M, int64_t inter, int64_t K,
                                        const uint8_t* a, int64_t lda, const float* sa, int64_t sar, int64_t sak,
                                        const uint8_t* b, int64_t ldb, const float* sb, uint8_t* q, int64_t ldq, float* s,
-                                       int64_t sor, int64_t sok, void* stream) {
+                                       int64_t sor, int64_t sok, void* workspace, size_t workspace_bytes, void* stream) {
     if (G < 0 || M < 0 || inter < 0 || K < 0) return DS3_ERR_SHAPE;
     if (K % 128 || inter % 128) return DS3_ERR_SHAPE;
     if (G == 0 || M == 0 || inter == 0) return DS3_OK;
@@ -224,6 +224,7 @@ static ds3_status grouped_swiglu_quant(bool pow2, int32_t G, const int32_t* offs
     if (!a || !b || !sa || !sb || !offs) return DS3_ERR_NULL;
     if (lda < K || ldb < K) return DS3_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(b) || lda % 16 || ldb % 16) return DS3_ERR_ALIGN;
+    if (workspace && !aligned16(workspace)) return DS3_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DS3_ERR_ALIGN;
     if ((int64_t)G * N * ldb >= (1ll << 40)) return DS3_ERR_UNSUPPORTED;
     {
@@ -243,26 +244,29 @@ static ds3_status grouped_swiglu_quant(bool pow2, int32_t G, const int32_t* offs
     p.b_group_stride = N * ldb;
     p.sb_group_stride = (N / 128) * (K / 128);
     p.q_out = q; p.s_out = s; p.ldq = ldq; p.sor = sor; p.sok = sok; p.q_pow2 = pow2 ? 1 : 0;
-    return launch_gemm_swiglu_quant(p, pow2, static_cast<hipStream_t>(stream));
+    return launch_gemm_swiglu_quant(p, pow2, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t inter,
                                                 int64_t K, const uint8_t* a, int64_t lda, const float* sa,
                                                 int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b, int64_t ldb,
                                                 const float* sb, uint8_t* q, int64_t ldq, float* s, int64_t s_stride_row,
-                                                int64_t s_stride_kb, void* stream) {
+                                                int64_t s_stride_kb, void* workspace, size_t workspace_bytes, void* stream) {
     return grouped_swiglu_quant(false, G, group_offsets, total_rows, inter, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
-                                sb, q, ldq, s, s_stride_row, s_stride_kb, stream);
+                                sb, q, ldq, s, s_stride_row, s_stride_kb, workspace, workspace_bytes, stream);
 }
 
 ds3_status ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2(int32_t G, const int32_t* group_offsets, int64_t total_rows, int64_t inter,
                                                      int64_t K, const uint8_t* a, int64_t lda, const float* sa,
                                                      int64_t sa_stride_row, int64_t sa_stride_kb, const uint8_t* b,
                                                      int64_t ldb, const float* sb, uint8_t* q, int64_t ldq, float* s,
-                                                     int64_t s_stride_row, int64_t s_stride_kb, void* stream) {
+                                                     int64_t s_stride_row, int64_t s_stride_kb, void* workspace,
+                                                     size_t workspace_bytes, void* stream) {
     return grouped_swiglu_quant(true, G, group_offsets, total_rows, inter, K, a, lda, sa, sa_stride_row, sa_stride_kb, b, ldb,
-                                sb, q, ldq, s, s_stride_row, s_stride_kb, stream);
+                                sb, q, ldq, s, s_stride_row, s_stride_kb, workspace, workspace_bytes, stream);
 }
+
+size_t ds3_grouped_gemm_workspace_bytes(void) { return grouped_workspace_bytes(); }
 
 int ds3_gemm_num_variants(void) { return gemm_num_variants(); }
 

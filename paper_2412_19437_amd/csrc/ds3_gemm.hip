@@ -40,7 +40,8 @@ constexpr int kMaxGroups = 1023;                       // experts per grouped ca
 constexpr int kShareSkew = 6;                          // K-steps by which the two pieces of a halved tile differ, each way
 constexpr int kAuxDevice = 16;                         // cache policy of a buffer access: sc1, coherent across the device
 constexpr int kTailCounters = 64;                      // arrival counters per XCD (tail tiles < workgroups per XCD <= 64)
-constexpr size_t kCounterBytes = 8 * kTailCounters * sizeof(int);
+constexpr int kQueueInts = 64;                         // the grouped walk's tile queue: [XCD] {next ticket, workgroups done}
+constexpr size_t kCounterBytes = (8 * kTailCounters + kQueueInts) * sizeof(int);
 
 template <int BN_, int BM_, int WN_, int WM_, int NS_>
 struct Cfg {
@@ -140,6 +141,27 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     const int ntiles = tiles_m * p.tiles_n;
     const int per_xcd = (ntiles + 7) >> 3;
     const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3), nslots = (int)(gridDim.x >> 3);
+    // Grouped walk with a workspace: the tiles of an XCD's chunk beyond the first round are handed
+    // out through a ticket counter, so a workgroup that drew cheap tiles (few valid rows) takes
+    // more of them.  Which workgroup computes a tile does not change its result.  A ticket is
+    // drawn when a tile starts and read after its K-loop; the last workgroup of the XCD to run
+    // out of work puts both counters back to zero for the next call.
+    [[maybe_unused]] const bool dyn = GROUPED && p.ws_cnt != nullptr;
+    [[maybe_unused]] int* const queue = p.ws_cnt + 8 * kTailCounters + xcd * 2;
+    [[maybe_unused]] int* const ticket_s = reinterpret_cast<int*>(sbrow_s);   // (per-row scale staging is unused here)
+    [[maybe_unused]] int dyn_local = slot;
+    [[maybe_unused]] const int cnt_xcd = max(0, min(per_xcd, ntiles - xcd * per_xcd));
+    auto leave_queue = [&]() {
+        if constexpr (GROUPED) {
+            if (dyn && tid == 0) {
+                const int d = __hip_atomic_fetch_add(queue + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (d == nslots - 1) {
+                    __hip_atomic_store(queue, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(queue + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+    };
     // The XCD's tiles are taken in rounds of one tile per workgroup.  What is left
     // after the last full round (`tail` tiles, fewer than workgroups) is either
     //  * shared along K: the tail's K-steps, tile after tile, are cut into equal
@@ -204,10 +226,13 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     };
 
     auto setup_unit = [&](int u, TileCtx& c) -> bool {
-        if (u >= w_units) return false;
         int half = -1, local;                          // local: index of the tile inside the XCD's chunk
         c.kb0 = 0; c.kb1 = KB;
-        if (u < w_rounds) local = u * nslots + slot;
+        if (GROUPED && dyn) {
+            if (dyn_local >= cnt_xcd) return false;
+            local = dyn_local;
+        } else if (u >= w_units) return false;
+        else if (u < w_rounds) local = u * nslots + slot;
         else if (!GROUPED && w_mode == kShareK) {
             const Tail w = load_tail();
             const int tt = u == w_rounds ? w.pt0 : w.pt1;   // first / second piece of this workgroup
@@ -346,7 +371,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
 
     TileCtx cur;
     int unit = 0;
-    if (!setup_unit(unit, cur)) return;
+    if (!setup_unit(unit, cur)) { leave_queue(); return; }
     // Workgroup barrier that lets the newest `pending` vector-memory operations of this
     // wave stay in flight (the loads that run more than one K-step ahead); LDS
     // operations are all complete when it returns.
@@ -380,6 +405,10 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
     for (;;) {
         // ---- entry: K-steps 0 .. NS-2 of `cur` (codes and scales) are in flight into stages 0 .. NS-2 ----
         __syncthreads();
+        [[maybe_unused]] int ticket = 0;
+        if constexpr (GROUPED) {
+            if (dyn && tid == 0) ticket = __hip_atomic_fetch_add(queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         // the part of K-step NS-1 that a previous K-step's barrier would have issued
 #pragma unroll
         for (int i = 0; i < C::TAILN; ++i)
@@ -572,7 +601,13 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         if (!active) kloop(kstep_idle);
         else if constexpr (POW2) kloop(kstep_p2);
         else kloop(kstep);
+        if constexpr (GROUPED) {
+            if (dyn && tid == 0) ticket_s[0] = ticket;
+        }
         __syncthreads();                               // every wave is done with all code stages
+        if constexpr (GROUPED) {
+            if (dyn) dyn_local = nslots + __builtin_amdgcn_readfirstlane(ticket_s[0]);
+        }
 
         // ---- the next tile's first K-steps fly into stages 0 .. NS-2 during this tile's epilogue ----
         // (what is read from LDS here is read before those loads are issued: the compiler makes an
@@ -850,6 +885,7 @@ __global__ __launch_bounds__(C::NT) void gemm_fp8_bs_kernel(const GemmParams p) 
         if (!more) break;
         cur = nxt;
     }
+    leave_queue();
 }
 
 // ---- host side -------------------------------------------------------------------
@@ -866,7 +902,8 @@ static int num_cus_x8() {
     return cached[dev];
 }
 
-__global__ void clear_counters_kernel(int* cnt) { cnt[threadIdx.x] = 0; }
+__global__ void clear_counters_kernel(int* cnt) { cnt[threadIdx.x] = 0; }     // one thread per counter
+static_assert(kCounterBytes / sizeof(int) <= 1024, "one workgroup clears the counters");
 
 // K-steps per workgroup when `tail` tiles of `kb` K-steps each are shared among `nslots`
 // workgroups as contiguous runs (workgroup s takes steps [s*q, (s+1)*q) of the tiles laid end
@@ -913,7 +950,9 @@ static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws
     const int64_t ntiles = (int64_t)p.tiles_m * p.tiles_n;
     const int64_t slots = (int64_t)num_cus_x8() * C::WG_PER_CU;
     int q_main = 0, q_last = 0, tail_max = 0;
-    const size_t need = GROUPED || ntiles <= 0 ? 0 : share_bytes<C>(ntiles, slots, p.K / 128, &q_main, &q_last, &tail_max);
+    // (the grouped walk needs the counters only: its tile queue)
+    const size_t need = ntiles <= 0 ? 0 : GROUPED ? kCounterBytes
+                                                  : share_bytes<C>(ntiles, slots, p.K / 128, &q_main, &q_last, &tail_max);
     if (ws_need) { *ws_need = need; return DS3_OK; }    // size query only
     if (ntiles <= 0) return DS3_OK;
     if (ntiles > (1 << 28)) return DS3_ERR_UNSUPPORTED;
@@ -928,7 +967,8 @@ static ds3_status launch_one(GemmParams p, void* ws, size_t ws_bytes, size_t* ws
     const int64_t want = ((ntiles + 7) / 8) * 8;
     const unsigned grid = (unsigned)(share || want > slots ? slots : want);
     (void)hipGetLastError();                            // a stale error of earlier, unrelated work is not this launch's
-    if (share) {
+    if (share && GROUPED) p.ws_cnt = static_cast<int*>(ws);
+    else if (share) {
         p.ws_cnt = static_cast<int*>(ws);
         p.ws_part = reinterpret_cast<float*>(static_cast<char*>(ws) + kCounterBytes);
         p.share_steps = q_main;
@@ -984,13 +1024,15 @@ ds3_status launch_gemm(const GemmParams& p, ds3_dtype ct, ds3_bscale mode, int v
                 : launch_variant<false>(p, ct, mode, variant, ws, ws_bytes, nullptr, st);
 }
 
-ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, hipStream_t st) {
+size_t grouped_workspace_bytes() { return kCounterBytes; }
+
+ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, void* ws, size_t ws_bytes, hipStream_t st) {
     // 256 weight rows per tile: the gate and the up half of one 1x128 output tile; 128 activation
     // rows and three stages, as the plain grouped GEMM runs by default
     using C = Cfg<256, 128, 4, 2, 3>;
     if (p.G <= 0 || p.N % 256) return DS3_ERR_SHAPE;
-    return pow2 ? launch_one<C, false, true, true, true, true>(p, nullptr, 0, nullptr, st)
-                : launch_one<C, false, true, true, false, true>(p, nullptr, 0, nullptr, st);
+    return pow2 ? launch_one<C, false, true, true, true, true>(p, ws, ws_bytes, nullptr, st)
+                : launch_one<C, false, true, true, false, true>(p, ws, ws_bytes, nullptr, st);
 }
 
 __global__ void zero_fill_kernel(uint8_t* c, int64_t row_bytes, int64_t ld_bytes, int64_t rows) {
@@ -1033,7 +1075,7 @@ static ds3_status scratch_address(void** out, hipStream_t st) {
         if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return DS3_ERR_LAUNCH;
         // the counters start even whatever ran before: once per device, in stream order before the first use
         (void)hipGetLastError();
-        clear_counters_kernel<<<dim3(1), dim3(8 * kTailCounters), 0, st>>>(static_cast<int*>(ptr));
+        clear_counters_kernel<<<dim3(1), dim3(kCounterBytes / sizeof(int)), 0, st>>>(static_cast<int*>(ptr));
         if (hipGetLastError() != hipSuccess) return DS3_ERR_LAUNCH;
         addr[dev] = ptr;
     }
@@ -1055,7 +1097,7 @@ ds3_status launch_workspace_init(void* ws, size_t ws_bytes, hipStream_t st) {
     if (ws_bytes < kCounterBytes) return DS3_ERR_WORKSPACE;
     (void)hipGetLastError();
     // a small kernel, not a memset: callers may capture this call into a graph
-    clear_counters_kernel<<<dim3(1), dim3(8 * kTailCounters), 0, st>>>(static_cast<int*>(ws));
+    clear_counters_kernel<<<dim3(1), dim3(kCounterBytes / sizeof(int)), 0, st>>>(static_cast<int*>(ws));
     return hipGetLastError() == hipSuccess ? DS3_OK : DS3_ERR_LAUNCH;
 }
 

@@ -76,7 +76,9 @@ ds3_status launch_gemm_static_scratch(const GemmParams& p, ds3_dtype ct, ds3_bsc
 size_t gemm_static_scratch_bytes();
 // Grouped GEMM over a gate|up weight interleaved in blocks of 128 rows, with SwiGLU and the 1x128
 // quantiser of the following Linear's input applied to each tile before it leaves the chip.
-ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, hipStream_t st);
+ds3_status launch_gemm_swiglu_quant(const GemmParams& p, bool pow2, void* ws, size_t ws_bytes, hipStream_t st);
+// Bytes of workspace with which the grouped GEMMs hand their tiles out through a queue (its counters).
+size_t grouped_workspace_bytes();
 // Bytes of workspace with which launch_gemm shares tail tiles for this shape (0: it would not).
 size_t gemm_workspace_bytes(const GemmParams& p, ds3_bscale mode, int variant);
 // K-steps per workgroup for a shared tail (see ds3_gemm.hip); host logic, exported for its test.

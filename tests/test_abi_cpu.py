@@ -89,7 +89,8 @@ def test_gemm_workspace_contract_on_the_host(pkg):
     L = pkg._L()
     buf = (ctypes.c_uint8 * 4096)()
     p = (ctypes.addressof(buf) + 15) & ~15
-    counters = 8 * 64 * 4
+    counters = (8 * 64 + 64) * 4                   # arrival counters of shared tiles + the grouped walk's tile queue
+    assert L.ds3_grouped_gemm_workspace_bytes() == counters
 
     def need(shared_tiles_per_xcd, tile_floats):   # arrival counters + two FP32 partial tiles per shared tile
         return counters + 8 * shared_tiles_per_xcd * 2 * tile_floats * 4
@@ -172,7 +173,7 @@ def test_later_entry_points_reject_bad_arguments_on_the_host(pkg):
     assert sq(p, 4, 16, 24, p, 16, p, 1, 4, None) == 2                        # ldh < 2 * inter
     assert sq(p, 4, 16, 32, None, 16, p, 1, 4, None) == 1
     for gq in (L.ds3_grouped_gemm_swiglu_quant_fp8_bs, L.ds3_grouped_gemm_swiglu_quant_fp8_bs_pow2):
-        ok = (2, p, 32, 128, 128, p, 128, p, 1, 32, p, 128, p, p, 128, p, 1, 32, None)
+        ok = (2, p, 32, 128, 128, p, 128, p, 1, 32, p, 128, p, p, 128, p, 1, 32, None, 0, None)
 
         def with_(i, v):
             return ok[:i] + (v,) + ok[i + 1:]

@@ -171,6 +171,39 @@ def test_grouped_small_with_empty_and_ragged_groups(ds3):
             assert np.array_equal(d, c[lo:hi]), (v, gi)
 
 
+def test_grouped_tile_queue_matches_the_static_walk(ds3):
+    """With a workspace the grouped GEMM hands its tiles out through a queue; which workgroup computes
+    a tile must not change a bit.  The counters are left ready: calls in a row, a dense call that
+    shares tail tiles through the same workspace in between, and a smaller problem afterwards."""
+    rng = np.random.default_rng(47)
+    sizes = rng.integers(0, 900, 48)
+    sizes[[0, 5, 47]] = 0
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    total, n, k, g = int(off[-1]), 1024, 512, len(sizes)
+    a, b = _rand_codes(rng, (total, k)), _rand_codes(rng, (g, n, k))
+    sa = np.exp(rng.standard_normal((total, k // 128))).astype(np.float32)
+    sb = np.exp(rng.standard_normal((g, n // 128, k // 128))).astype(np.float32)
+    args = (dev(a), _kmajor(sa), dev(off), dev(b), dev(sb))
+    nbytes = max(ds3._L().ds3_grouped_gemm_workspace_bytes(), ds3.ds3_gemm_workspace_bytes_v(0, 1024, 1024, 1024))
+    ws = ds3.new_gemm_workspace(nbytes, "cuda:0")
+    for v in _variants(ds3):
+        announce(f"grouped tile queue variant {v}")
+        static = ds3.ds3_grouped_gemm_fp8_bs(*args, variant=v, workspace=None)
+        for rep in range(3):
+            assert torch.equal(static, ds3.ds3_grouped_gemm_fp8_bs(*args, variant=v, workspace=ws)), (v, rep)
+        # a dense call that shares its tail tiles along K through the same workspace
+        da, db = _rand_codes(rng, (1024, 1024)), _rand_codes(rng, (1024, 1024))
+        dsa, dsb = np.ones((1024, 8), np.float32), np.ones((8, 8), np.float32)
+        d = host(ds3.ds3_gemm_fp8_bs(dev(da), dev(dsa), dev(db), dev(dsb), out_dtype=torch.float32, variant=0, workspace=ws))
+        assert normwise(d, orc.gemm_fp8_bs(da, dsa, db, dsb)) <= TOL_F32
+        # fewer tiles than workgroups: most workgroups leave the queue without a tile
+        few = (args[0][:300], args[1][:300], dev(np.array([0, 3, 300], np.int32)), args[3][:2], args[4][:2])
+        assert torch.equal(ds3.ds3_grouped_gemm_fp8_bs(*few, variant=v, workspace=None),
+                           ds3.ds3_grouped_gemm_fp8_bs(*few, variant=v, workspace=ws))
+        assert torch.equal(static, ds3.ds3_grouped_gemm_fp8_bs(*args, variant=v, workspace=ws))
+    assert normwise(host(static)[:total], orc.grouped_gemm_fp8_bs(a, sa, off, b, sb)) <= TOL_BF16
+
+
 def test_grouped_many_experts_exact(ds3):
     """40 experts with sizes from 0 to several row tiles, small-integer codes and
     power-of-two scales: the grouped FP32 output equals the oracle bit for bit."""

@@ -109,7 +109,7 @@ def test_exact_gemm_stage_and_untouched_rows(ds3):
     ad, sad, offd = dev(a), _kmajor(sa), dev(off)
     st = L.ds3_grouped_gemm_swiglu_quant_fp8_bs(g, offd.data_ptr(), m, inter, k, ad.data_ptr(), k, sad.data_ptr(),
                                                 sad.stride(0), sad.stride(1), bi.data_ptr(), k, sbi.data_ptr(),
-                                                q.data_ptr(), inter, s.data_ptr(), s.stride(0), s.stride(1),
+                                                q.data_ptr(), inter, s.data_ptr(), s.stride(0), s.stride(1), None, 0,
                                                 torch.cuda.current_stream().cuda_stream)
     assert st == 0
     qh, sh = host(q), host(s)
