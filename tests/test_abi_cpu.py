@@ -120,6 +120,16 @@ def test_gemm_workspace_contract_on_the_host(pkg):
     assert call(p, 0) == 7
     assert call(p + 4, need) == 3                 # misaligned workspace
     assert pkg.status_string(7).startswith("workspace")
+    # the grouped calls: a workspace smaller than their tile queue's counters is refused, a misaligned one too
+    def grouped(ws, nbytes):
+        return L.ds3_grouped_gemm_fp8_bs(2, p, 512, 256, 256, p, 256, p, 1, 512, p, 256, p, p, 1, 256, ws, nbytes, None)
+
+    def grouped_swiglu(ws, nbytes):
+        return L.ds3_grouped_gemm_swiglu_quant_fp8_bs(2, p, 512, 128, 256, p, 256, p, 1, 512, p, 256, p, p, 128, p, 1, 512,
+                                                      ws, nbytes, None)
+    for f in (grouped, grouped_swiglu):
+        assert f(p, counters - 1) == 7 and f(p, 0) == 7
+        assert f(p + 4, counters) == 3
 
 
 def test_tail_share_steps_never_cuts_a_tile_in_three(pkg):
