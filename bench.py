@@ -212,7 +212,8 @@ def machine_probes(ds3, torch, dev):
     return {"library_context": lib, "mfma_fp8_register_loop_tflops": mfma, "mfma_fp8_register_loop_frac_of_peak": mfma / PEAK_FP8_TFLOPS,
             "l2_to_lds_feed_gbs_per_cu": feed, "l2_to_lds_feed_tbs_total": feed * cus / 1e3,
             "feed_needed_gbs_per_cu_at_register_loop_rate": 65536.0 / (2.0 * 256 * 256 * 128 / (mfma * 1e12 / cus)) / 1e9,
-            "note": "a 256x256 FP8 tile consumes 64 KiB of operands per 128-deep K-step (2*256*256*128 flop)"}
+            "note": "a 256x256 FP8 tile consumes 64 KiB of operands per 128-deep K-step (2*256*256*128 flop); the feed probe "
+                    "keeps one K-step of LDS-bound loads queued behind the one it waits for, as the GEMM does"}
 
 
 def cpu_baseline(wl):

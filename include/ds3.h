@@ -487,7 +487,8 @@ ds3_status ds3_adamw_bf16_states(int64_t n, float* master_w, const float* grad, 
  * ds3_probe_lds_feed: every workgroup moves iters * 64 KiB from `src` (DEVICE,
  * window_bytes < 2^31, rows of 128 bytes taken at `row_stride` bytes, a
  * multiple of 128, window_bytes >= 4096 * row_stride) into LDS with the
- * GEMM's load pattern.  out: DEVICE, `workgroups` words.
+ * GEMM's load pattern, one step's loads queued behind the step it waits for.
+ * out: DEVICE, `workgroups` words.
  */
 ds3_status ds3_probe_mfma_fp8(int iters, int workgroups, float* out, void* stream);
 ds3_status ds3_probe_lds_feed(const void* src, size_t window_bytes, int64_t row_stride, int iters, int workgroups,

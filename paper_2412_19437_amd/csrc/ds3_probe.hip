@@ -41,7 +41,9 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(float* out, int iters, 
 
 // Every workgroup (one per compute unit, 512 threads) streams 512 rows x 128 bytes per
 // step -- the footprint of one K-step of a 256x256 tile -- from an L2-resident window
-// into two alternating LDS stages with 16-byte LDS-direct loads, a barrier per step.
+// into two alternating LDS stages with 16-byte LDS-direct loads, a barrier per step.  The
+// loads of the next step are queued before the barrier waits for this step's (as the GEMM
+// does): with nothing queued the figure is one L2 latency per step, not a feed rate.
 __global__ __launch_bounds__(512) void probe_feed_kernel(const uint8_t* src, unsigned window, int row_stride, int iters,
                                                          unsigned* out) {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * 65536];
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(512) void probe_feed_kernel(const uint8_t* src, uns
     __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)src, 0, (int)window, 0x00020000);
     const unsigned panel = (blockIdx.x >> 3) & 7;                       // workgroups of an XCD share 8 row panels
     const unsigned voff0 = (panel * 512 + (tid >> 3)) * (unsigned)row_stride + (tid & 7) * 16;
-    for (int it = 0; it < iters; ++it) {
+    auto issue = [&](int it) {
         const unsigned kofs = ((unsigned)it * 128u) % (unsigned)row_stride;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -58,8 +60,17 @@ __global__ __launch_bounds__(512) void probe_feed_kernel(const uint8_t* src, uns
             // offsets beyond the window are range-checked by the descriptor and move no data
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)dst, 16, (int)(voff0 + i * 64 * row_stride + kofs), 0, 0, 0);
         }
-        __syncthreads();
+    };
+    issue(0);
+    for (int it = 0; it < iters; ++it) {
+        issue(it + 1);                                 // (one step more than asked for: it moves data nobody reads)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(8 | 0x70);          // vmcnt(8): step `it` has landed, step it+1 stays in flight
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     }
+    __builtin_amdgcn_s_waitcnt(0x70);                  // vmcnt(0)
+    __syncthreads();
     const u32x4 v = *reinterpret_cast<const u32x4*>(smem + tid * 16);
     if (tid == 0) out[blockIdx.x] = v.x ^ v.y ^ v.z ^ v.w;
 }
