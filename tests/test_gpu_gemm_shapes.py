@@ -84,3 +84,36 @@ def test_seeded_grouped_sweep(ds3):
         got = host(c)
         assert np.array_equal(got[: off[-1]].astype(np.float64), ref), case
         assert np.all(got[off[-1]:] == -3.0), "rows beyond the last group were written"
+
+
+def test_seeded_grouped_sweep(ds3):
+    """The same for the grouped GEMM: random group sizes (empty, single rows, around the tile heights),
+    ragged N, every tile configuration, both scale paths, static walk and tile queue, rows beyond the
+    last group untouched -- bit for bit against the oracle."""
+    rng = np.random.default_rng(2025)
+    nvar = ds3.ds3_gemm_num_variants()
+    for case in range(24):
+        g = int(rng.integers(1, 13))
+        sizes = rng.choice([0, 0, 1, 5, 64, 65, 127, 128, 129, 200, 256, 257, 300], g)
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        total, extra = int(off[-1]), int(rng.integers(0, 4))
+        n = int(rng.choice([64, 128, 200, 256, 384, 640]))
+        k = 128 * int(rng.integers(1, 7))
+        pow2 = bool(rng.integers(0, 2))
+        variant = int(rng.integers(-1, nvar))
+        queue = bool(rng.integers(0, 2))
+        announce(f"grouped sweep {case}: sizes {list(sizes)} n={n} k={k} pow2={pow2} variant={variant} queue={queue}")
+        rows = total + extra
+        a, b = TABLE[rng.integers(0, 6, (max(rows, 1), k))], TABLE[rng.integers(0, 6, (g, n, k))]
+        sa = np.ldexp(1.0, rng.integers(-2, 2, (max(rows, 1), k // 128))).astype(np.float32)
+        sb = np.ldexp(1.0, rng.integers(-1, 3, (g, (n + 127) // 128, k // 128))).astype(np.float32)
+        ref = orc.grouped_gemm_fp8_bs(a[:total], sa[:total], off, b, sb)
+        ldc = (n + 3) // 4 * 4
+        cbuf = torch.full((max(rows, 1), ldc), 7.0, dtype=torch.float32, device="cuda:0")
+        c = cbuf[:, :n]
+        fn = ds3.ds3_grouped_gemm_fp8_bs_pow2 if pow2 else ds3.ds3_grouped_gemm_fp8_bs
+        fn(dev(a), dev(np.ascontiguousarray(sa.T)).t(), dev(off), dev(b), dev(sb), c=c, variant=variant,
+           workspace="auto" if queue else None)
+        got = host(cbuf)
+        assert np.array_equal(got[:total, :n].astype(np.float64), ref), case
+        assert np.all(got[total:] == 7.0) and np.all(got[:, n:] == 7.0), case
