@@ -83,3 +83,22 @@ def test_gemm_with_a_4_gb_output(ds3):
             continue
         g = 0 if r < 30_000 else 2
         assert normwise(got[i], ref[i, g * 8192:(g + 1) * 8192]) <= 2 * TOL_BF16, int(r)
+
+
+def test_gemm_with_a_very_long_inner_dimension(ds3):
+    """K = 65536 (512 K-steps): small-integer codes and power-of-two scales keep every partial sum exact,
+    so the FP32 result equals the oracle bit for bit; with and without tail sharing, both scale paths."""
+    m, n, k = 300, 260, 65_536
+    announce(f"long K {m}x{n}x{k}")
+    rng = np.random.default_rng(9005)
+    table = np.array([0x00, 0x38, 0x40, 0xB8, 0xC0, 0x80], dtype=np.uint8)   # 0, 1, 2, -1, -2, -0
+    a, b = table[rng.integers(0, 6, (m, k))], table[rng.integers(0, 6, (n, k))]
+    sa = np.ldexp(1.0, rng.integers(-1, 2, (m, k // 128))).astype(np.float32)
+    sb = np.ldexp(1.0, rng.integers(-1, 3, ((n + 127) // 128, k // 128))).astype(np.float32)
+    ref = orc.gemm_fp8_bs(a, sa, b, sb)
+    assert np.array_equal(ref.astype(np.float32).astype(np.float64), ref)
+    args = (dev(a), dev(np.ascontiguousarray(sa.T)).t(), dev(b), dev(sb))
+    for fn in (ds3.ds3_gemm_fp8_bs, ds3.ds3_gemm_fp8_bs_pow2):
+        for ws in ("auto", None):
+            c = host(fn(*args, out_dtype=torch.float32, workspace=ws))
+            assert np.array_equal(c.astype(np.float64), ref), (fn.__name__, ws)
