@@ -19,7 +19,7 @@ TOL_F32 = 1e-4
 BF16_IDENTICAL = 0.96
 
 
-def _check_bf16(what, got, a, sa, b, sb):
+def _check_bf16(what, got, a, sa, b, sb, identical=BF16_IDENTICAL):
     """Normwise bar, and element by element: half a BF16 ulp of output rounding plus the
     accumulation bound, with nearly all outputs equal to the rounded reference."""
     ref = orc.gemm_fp8_bs(a, sa, b, sb)
@@ -27,7 +27,7 @@ def _check_bf16(what, got, a, sa, b, sb):
     excess, same = bf16_elementwise(got, ref, magnitude_sum(a, sa, b, sb))
     print(f"{what}: normwise {e:.3e}; worst (|err| - accumulation bound) = {excess:.3f} BF16 ulp; {100 * same:.2f}% equal the rounded reference")
     assert e <= TOL_BF16, what
-    assert excess <= 0.5 and same >= BF16_IDENTICAL, what
+    assert excess <= 0.5 and same >= identical, what
 
 
 def _expert_weights(g, shape, tensor_index, sampled, expert_fn, ids=None):
@@ -169,3 +169,44 @@ def test_cfg5_mla_full_size_sampled(ds3):
         rng = np.random.default_rng(49 + idx)
         pick = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, 8)]))
         _check_bf16(f"cfg5 {name} {m}x{n}x{k}", host(c[torch.from_numpy(pick).to("cuda:0")]), host(qa)[pick], host(sa)[pick], host(qb), host(sb))
+
+
+def test_cfg2_cfg4_pow2_full_size_sampled(ds3):
+    """The power-of-two path at the benchmark's sizes: Fprop 4096 x 18432 x 7168 (BF16 and FP32 out) and
+    Wgrad 18432 x 7168 x 4096 with per-row scales and FP32 accumulation, scales applied by the matrix
+    instruction; quantizer outputs bit for bit, GEMM outputs on sampled rows."""
+    announce("cfg2/cfg4 pow2 full size sampled")
+    x, w = wl.cfg2_x(), wl.cfg2_w()
+    qa, sa = ds3.ds3_quant_act_1x128_pow2(dev(x, bf16=True))
+    qb, sb = ds3.ds3_quant_w_128x128_pow2(dev(w, bf16=True))
+    rng = np.random.default_rng(49)
+    rows = np.unique(np.concatenate([[0, 255, 256, 4095], rng.integers(0, 4096, 12)]))
+    q_ref, s_ref = orc.quant_act_1x128(x[rows], pow2=True)
+    qa_h, sa_h, qb_h, sb_h = host(qa), host(sa), host(qb), host(sb)
+    assert np.array_equal(qa_h[rows], q_ref) and np.array_equal(sa_h[rows], s_ref)
+    qw_ref, sw_ref = orc.quant_w_128x128(w[:256], pow2=True)
+    assert np.array_equal(qb_h[:256], qw_ref) and np.array_equal(sb_h[:2], sw_ref)
+    del w
+    c = host(ds3.ds3_gemm_fp8_bs_pow2(qa, sa, qb, sb))
+    # (the matrix unit adds every block's sum to the running FP32 total itself: its accumulation error is
+    # carried along K instead of being renewed per block, and a little more of the outputs land on the other
+    # side of a BF16 rounding boundary: 96.4% identical here against 97-99% on the general path)
+    _check_bf16("cfg2 pow2 sampled rows", c[rows], qa_h[rows], sa_h[rows], qb_h, sb_h, identical=0.94)
+    c32 = ds3.ds3_gemm_fp8_bs_pow2(qa, sa, qb, sb, out_dtype=torch.float32)
+    e32 = normwise(host(c32[torch.from_numpy(rows).to("cuda:0")]), orc.gemm_fp8_bs(qa_h[rows], sa_h[rows], qb_h, sb_h))
+    print(f"cfg2 pow2 FP32 out: {e32:.3e}")
+    assert e32 <= TOL_F32
+    del c, c32, qa, sa, qb, sb
+    # Wgrad
+    dy = wl.cfg4_dy()
+    qyt, syt = ds3.ds3_quant_act_128x1_pow2(dev(dy, bf16=True))
+    qxt, sxt = ds3.ds3_quant_act_128x1_pow2(dev(x, bf16=True))
+    del x, dy
+    dw = torch.full((wl.DENSE_INTER, wl.HIDDEN), 0.25, dtype=torch.float32, device="cuda:0")
+    ds3.ds3_gemm_fp8_bs_pow2(qyt, syt, qxt, sxt, sb_mode=ds3.DS3_BSCALE_PER_ROW, c=dw, accumulate=True)
+    pick = np.unique(np.concatenate([[0, 255, 256, 18431], rng.integers(0, wl.DENSE_INTER, 12)]))
+    ref = orc.gemm_fp8_bs(host(qyt)[pick], host(syt)[pick], host(qxt), host(sxt), sb_per_row=True,
+                          c_in=np.full((len(pick), wl.HIDDEN), 0.25))
+    e = normwise(host(dw[torch.from_numpy(pick).to("cuda:0")]), ref)
+    print(f"cfg4 pow2 wgrad sampled: {e:.3e}")
+    assert e <= TOL_F32
